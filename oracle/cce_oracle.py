@@ -1,0 +1,149 @@
+"""fp64 CPU oracle for the fused LM-head + cross-entropy path.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the HIP
+library is checked against.  It shares no code with the GPU path, imports
+nothing from the package, and must never be called from the product path; only
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg use it.
+
+What it computes, and where the paper defines it:
+
+* logits           Z = H W^T (language-model head without bias; chunked-forward
+                   algorithm of the Cut Cross-Entropy section, the step that forms
+                   the partial logits of a vocabulary chunk)
+* log-sum-exp      lse_i = m_i + ln sum_v exp(Z_iv - m_i), m_i = max_v Z_iv
+                   (stable log-sum-exp, numerical-stability appendix; the online
+                   softmax correctness theorem states that the streamed recurrence
+                   reaches exactly this value, so the oracle is the plain formula)
+* per-token loss   L_i = lse_i - Z_{i,y_i}        (cross-entropy definition in the
+                   mathematical-foundations section; restated in the CCE section)
+* logit gradient   dL_i/dZ_iv = softmax(Z_i)_v - 1[v = y_i]   (cross-entropy
+                   gradient proposition; CCE backward theorem)
+* input gradients  dH = G W,  dW = G^T H  with  G_iv = dloss_i * dL_i/dZ_iv
+                   (chunk-level backward algorithm of the CCE section, summed
+                   over all chunks)
+
+Readings taken where the paper is silent (each is listed in the design notes):
+rows whose label equals ``ignore_index`` give loss 0, lse 0 and contribute
+exactly nothing to either gradient whatever their ``dloss`` holds (the forward
+kernel listing stores 0 and returns for such rows); the upstream gradient is
+a per-token factor; labels outside [0, V) other than ``ignore_index`` are an
+error.  No bias, no label shift, no logit scaling or soft-capping.
+
+Inputs are bf16 bit patterns (``uint16``); they are widened exactly to float64
+and every operation after that is float64.  Row blocking only bounds memory:
+each block still materialises its full [rows x V] logits.
+
+All functions are pinned by tests/test_oracle_pins.py against closed forms,
+invariants, a brute-force loop, central finite differences and
+``torch.nn.functional.cross_entropy`` (float64, CPU, with autograd).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "widen_bf16", "logits", "forward", "grad_logits", "backward",
+    "logit_memory_bytes", "chunk_reduction_factor",
+]
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float64, exactly."""
+    bits = np.asarray(bits)
+    if bits.dtype != np.uint16:
+        raise TypeError("bf16 tensors are passed as uint16 bit patterns")
+    as_f32 = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return as_f32.astype(np.float64)
+
+
+def _check(hidden_bits, weight_bits, labels, ignore_index):
+    if hidden_bits.ndim != 2 or weight_bits.ndim != 2:
+        raise ValueError("hidden is [N, D], weight is [V, D]")
+    N, D = hidden_bits.shape
+    V, D2 = weight_bits.shape
+    if D != D2:
+        raise ValueError("hidden and weight disagree on D")
+    labels = np.asarray(labels)
+    if labels.shape != (N,):
+        raise ValueError("labels is [N]")
+    valid = labels != ignore_index
+    lab = labels[valid]
+    if lab.size and (lab.min() < 0 or lab.max() >= V):
+        raise ValueError("label outside [0, V) that is not ignore_index")
+    return N, D, V, valid
+
+
+def logits(hidden_bits: np.ndarray, weight_bits: np.ndarray) -> np.ndarray:
+    """Z[i, v] = sum_k H[i, k] W[v, k] in float64, fully materialised."""
+    return widen_bf16(hidden_bits) @ widen_bf16(weight_bits).T
+
+
+def _lse_rows(Z: np.ndarray) -> np.ndarray:
+    m = Z.max(axis=1)
+    return m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+
+
+def forward(hidden_bits, weight_bits, labels, ignore_index=-100, row_block=1024):
+    """Per-token loss and log-sum-exp, float64 [N] each.
+
+    Ignored rows: loss = lse = 0 exactly.
+    """
+    N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
+    W = widen_bf16(weight_bits)
+    loss = np.zeros(N, dtype=np.float64)
+    lse = np.zeros(N, dtype=np.float64)
+    for r0 in range(0, N, row_block):
+        r1 = min(N, r0 + row_block)
+        Z = widen_bf16(hidden_bits[r0:r1]) @ W.T
+        l = _lse_rows(Z)
+        vb = valid[r0:r1]
+        idx = np.nonzero(vb)[0]
+        zy = Z[idx, labels[r0:r1][idx]]
+        lse[r0 + idx] = l[idx]
+        loss[r0 + idx] = l[idx] - zy
+    return loss, lse
+
+
+def grad_logits(hidden_bits, weight_bits, labels, dloss, ignore_index=-100):
+    """G[i, v] = dloss_i * (softmax(Z_i)_v - 1[v = y_i]); zero rows where ignored.
+
+    Materialises [N x V]: for small inputs or row subsets.
+    """
+    N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
+    Z = logits(hidden_bits, weight_bits)
+    l = _lse_rows(Z)
+    P = np.exp(Z - l[:, None])
+    idx = np.nonzero(valid)[0]
+    P[idx, np.asarray(labels)[idx]] -= 1.0
+    g = np.where(valid, np.asarray(dloss, dtype=np.float64), 0.0)   # select, not multiply
+    G = P * g[:, None]
+    G[~valid] = 0.0
+    return G
+
+
+def backward(hidden_bits, weight_bits, labels, dloss, ignore_index=-100, row_block=1024):
+    """dH [N, D] and dW [V, D] in float64 for upstream per-token gradient dloss [N]."""
+    N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
+    W = widen_bf16(weight_bits)
+    dH = np.zeros((N, D), dtype=np.float64)
+    dW = np.zeros((V, D), dtype=np.float64)
+    for r0 in range(0, N, row_block):
+        r1 = min(N, r0 + row_block)
+        Hb = widen_bf16(hidden_bits[r0:r1])
+        G = grad_logits(hidden_bits[r0:r1], weight_bits, np.asarray(labels)[r0:r1],
+                        np.asarray(dloss)[r0:r1], ignore_index)
+        dH[r0:r1] = G @ W
+        dW += G.T @ Hb
+    return dH, dW
+
+
+def logit_memory_bytes(B: int, N: int, V: int, bytes_per_logit: int = 4) -> int:
+    """Size of the materialised logit tensor: B x N x V x 4 bytes (memory-bottleneck
+    definition at the start of the CCE section)."""
+    return B * N * V * bytes_per_logit
+
+
+def chunk_reduction_factor(V: int, C: int) -> float:
+    """Memory reduction of chunking the vocabulary into pieces of C: V / C
+    (CCE memory-reduction theorem)."""
+    return V / C
