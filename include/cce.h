@@ -1,0 +1,123 @@
+/*
+ * libcce -- fused language-model-head projection + token-level cross-entropy for
+ * AMD MI355X (gfx950), forward and backward, without ever materialising the
+ * [tokens x vocab] logit tensor.
+ *
+ * The operation is the paper's Cut Cross-Entropy (section "Cut Cross-Entropy:
+ * Memory-Efficient Loss Computation"):
+ *   forward  -- chunked cross-entropy forward algorithm; per-token
+ *               loss_i = logsumexp_v(h_i . W_v) - h_i . W_{y_i}
+ *               (cross-entropy definition; the running (max, sum-exp) pair is the
+ *               online-softmax definition, whose correctness theorem makes the
+ *               result independent of how the vocabulary is tiled);
+ *   backward -- CCE backward theorem and chunk-level backward algorithm:
+ *               G_iv = dloss_i * (exp(h_i . W_v - lse_i) - [v == y_i]),
+ *               dH = G W,  dW = G^T H, with the logits recomputed tile by tile.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates, frees or retains device memory and never synchronises the
+ *     stream in the compute calls.  Tensors are dense row-major: hidden [N, D],
+ *     weight [V, D] (no bias), labels [N], loss/lse/dloss [N], dHidden [N, D],
+ *     dW [V, D].  Pointers must be 16-byte aligned.
+ *   - bf16 tensors are raw 16-bit patterns (`void*`); fp32 tensors are `float*`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it, in order.
+ *   - D must be a positive multiple of 64 (the K granule of the MFMA main loop);
+ *     N, V >= 1 are otherwise arbitrary (ragged tiles are masked).
+ *   - A row whose label equals `ignore_index` yields loss = lse = 0, a zero dHidden
+ *     row and no contribution to dW, whatever hidden/dloss hold for it.  A label
+ *     outside [0, V) that is not `ignore_index` is treated the same way and sets
+ *     CCE_STATUS_BAD_LABEL in the workspace status word (see cce_read_status).
+ *   - Every call returns CCE_OK (0) or a negative error code; nothing throws or
+ *     aborts across this boundary.  On an error return nothing was enqueued.
+ *   - `workspace` is caller-owned device scratch of at least
+ *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
+ *     O(N*D + tile): per-row partial (max, sum-exp) pairs, an fp32 dHidden
+ *     accumulator for one row block and one bf16 [row block x vocab chunk]
+ *     gradient tile; it never scales with N*V.  Contents are scratch: nothing
+ *     needs to survive between forward and backward except what the caller
+ *     passes explicitly (lse).
+ */
+#ifndef CCE_H_
+#define CCE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CCE_OK = 0,
+    CCE_ERR_INVALID = -1,      /* null pointer, N/D/V <= 0, misaligned pointer, workspace too small */
+    CCE_ERR_UNSUPPORTED = -2,  /* D not a multiple of 64, or a size beyond 32-bit tile indexing */
+    CCE_ERR_HIP = -3           /* a HIP call or kernel launch failed (see cce_last_hip_error) */
+};
+
+enum {
+    CCE_STATUS_BAD_LABEL = 1   /* some label was outside [0, V) and not ignore_index */
+};
+
+/* Library version, "major.minor.patch". Host only. */
+const char* cce_version(void);
+
+/* Text for an error code. Host only; the returned string is static. */
+const char* cce_strerror(int code);
+
+/* hipError_t (as int) of the last failed HIP call made by this thread, 0 if none. */
+int cce_last_hip_error(void);
+
+/* Bytes of device workspace needed by cce_forward / cce_backward for this shape.
+ * Pure host function (queries the current device's CU count once); returns 0 for
+ * invalid shapes. */
+size_t cce_workspace_bytes(int64_t N, int64_t D, int64_t V);
+
+/* Size N*V*4 of the logit tensor that is NOT materialised (the paper's memory
+ * equation for the logits: tokens x vocab x 4 bytes), for reporting the workspace
+ * as a fraction of it. */
+size_t cce_materialised_logit_bytes(int64_t N, int64_t V);
+
+/*
+ * Forward (chunked cross-entropy forward algorithm; forward kernel listing).
+ *   hidden  in  bf16 [N, D]    device
+ *   weight  in  bf16 [V, D]    device
+ *   labels  in  int32 [N]      device
+ *   loss    out fp32 [N]       device   loss_i = lse_i - h_i . W_{y_i}; 0 for ignored rows
+ *   lse     out fp32 [N]       device   log-sum-exp of row i's logits; 0 for ignored rows
+ * Logit tiles are accumulated in fp32 and consumed unrounded; the label logit is an
+ * fp32 dot product of the bf16 inputs.
+ */
+int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
+                int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                float* loss, float* lse,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward (CCE backward theorem; chunk-level backward algorithm).
+ *   hidden, weight, labels, ignore_index, N, D, V   as in cce_forward
+ *   lse      in  fp32 [N]     device   as produced by cce_forward for the same inputs
+ *   dloss    in  fp32 [N]     device   upstream gradient of each per-token loss
+ *                                      (1/N_valid everywhere for a mean loss); entries
+ *                                      at ignored rows are never used (may be NaN)
+ *   dHidden  out bf16 [N, D]  device   fp32 accumulation, rounded to nearest even
+ *   dW       out fp32 [V, D]  device   accumulate_dW == 0: overwritten;
+ *                                      accumulate_dW != 0: the gradient is added to it
+ * The logit gradient tile is rounded to bf16 (nearest even) before the two
+ * contractions, which accumulate in fp32.
+ */
+int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
+                 const float* lse, const float* dloss,
+                 int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                 void* dHidden, float* dW, int accumulate_dW,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Copies the workspace status word (bit set of CCE_STATUS_*) to *status_out (host).
+ * Synchronises `stream`.  The word is cleared at the start of every cce_forward. */
+int cce_read_status(const void* workspace, void* stream, int32_t* status_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCE_H_ */

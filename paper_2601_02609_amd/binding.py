@@ -1,0 +1,165 @@
+"""ctypes binding of the libcce C ABI (include/cce.h).  Argument marshalling only.
+
+PyTorch is used for device memory and the current HIP stream; every step of the
+computation runs in the library's kernels.  There is no fallback: if the shared
+library has not been built the import of the library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from . import build as _build
+
+CCE_OK = 0
+CCE_ERR_INVALID = -1
+CCE_ERR_UNSUPPORTED = -2
+CCE_ERR_HIP = -3
+CCE_STATUS_BAD_LABEL = 1
+
+EXPORTED_SYMBOLS = [
+    "cce_version", "cce_strerror", "cce_last_hip_error", "cce_workspace_bytes",
+    "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
+]
+
+_lib = None
+
+
+class CCEError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().cce_strerror(code).decode()
+        hip = lib().cce_last_hip_error()
+        super().__init__(f"{where}: {msg} (code {code}, hip error {hip})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcce.so (built in-tree by paper_2601_02609_amd.build); raise if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(
+            f"{path} is missing: build it first (python -m paper_2601_02609_amd.build). "
+            "There is no CPU or PyTorch fallback for this library.")
+    L = ctypes.CDLL(path)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    L.cce_version.restype = ctypes.c_char_p
+    L.cce_version.argtypes = []
+    L.cce_strerror.restype = ctypes.c_char_p
+    L.cce_strerror.argtypes = [ctypes.c_int]
+    L.cce_last_hip_error.restype = ctypes.c_int
+    L.cce_last_hip_error.argtypes = []
+    L.cce_workspace_bytes.restype = sz
+    L.cce_workspace_bytes.argtypes = [i64, i64, i64]
+    L.cce_materialised_logit_bytes.restype = sz
+    L.cce_materialised_logit_bytes.argtypes = [i64, i64]
+    L.cce_forward.restype = ctypes.c_int
+    L.cce_forward.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+    L.cce_backward.restype = ctypes.c_int
+    L.cce_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_read_status.restype = ctypes.c_int
+    L.cce_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    _lib = L
+    return L
+
+
+def version() -> str:
+    return lib().cce_version().decode()
+
+
+def workspace_bytes(N: int, D: int, V: int) -> int:
+    return int(lib().cce_workspace_bytes(N, D, V))
+
+
+def materialised_logit_bytes(N: int, V: int) -> int:
+    return int(lib().cce_materialised_logit_bytes(N, V))
+
+
+def alloc_workspace(N: int, D: int, V: int, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(N, D, V)
+    if n == 0:
+        raise CCEError(CCE_ERR_UNSUPPORTED, "cce_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _check(t: torch.Tensor, dtype, shape, name):
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: expected contiguous cuda {dtype} {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)} contiguous={t.is_contiguous()} cuda={t.is_cuda}")
+
+
+def cce_forward(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,
+                ignore_index: int = -100, *, workspace: Optional[torch.Tensor] = None,
+                loss: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Per-token loss and log-sum-exp (fp32 [N] each) of bf16 hidden [N, D] x weight [V, D]."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden.device)
+    if loss is None:
+        loss = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    rc = lib().cce_forward(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), N, D, V,
+                           ignore_index, loss.data_ptr(), lse.data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_forward")
+    return loss, lse
+
+
+def cce_backward(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,
+                 lse: torch.Tensor, dloss: torch.Tensor, ignore_index: int = -100, *,
+                 workspace: Optional[torch.Tensor] = None,
+                 d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                 accumulate_dw: bool = False,
+                 stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """dHidden (bf16 [N, D]) and dW (fp32 [V, D]) for upstream per-token gradient dloss [N]."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(V, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (V, D), "d_weight")
+    rc = lib().cce_backward(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(),
+                            lse.data_ptr(), dloss.data_ptr(), N, D, V, ignore_index,
+                            d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_backward")
+    return d_hidden, d_weight
+
+
+def read_status(workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> int:
+    out = ctypes.c_int32(0)
+    rc = lib().cce_read_status(workspace.data_ptr(), _stream_ptr(stream), ctypes.byref(out))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_read_status")
+    return int(out.value)

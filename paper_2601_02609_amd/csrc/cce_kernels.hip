@@ -1,0 +1,577 @@
+// libcce: fused LM-head projection + token-level cross-entropy for gfx950 (MI355X).
+// Device kernels and the C ABI declared in include/cce.h.
+//
+// Forward (chunked cross-entropy forward algorithm of the Cut Cross-Entropy section):
+//   lse_partial_kernel   logit tile (MFMA) -> online (max, sum-exp) per token, carried in
+//                        registers across the vocabulary tiles of one split (online-softmax
+//                        definition); one (m, d) pair per token and split is written out
+//   finalize_kernel      merges the pairs of all splits (block form of the same recurrence),
+//                        lse = m + ln d, label logit by an fp32 dot product, loss = lse - z_y,
+//                        ignore_index rows -> 0
+// Backward (CCE backward theorem and chunk-level backward algorithm), for each
+// [row block x vocabulary chunk]:
+//   grad_tile_kernel     recomputes the logit tile, forms dloss * (exp(z - lse) - onehot),
+//                        rounds to bf16 and stores it in a scratch chunk G[rows][chunk]
+//   grad_gemm_kernel     dH_block += G * W_chunk   and   dW_chunk (+)= G^T * H_block
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <math.h>
+
+#include "../../include/cce.h"
+#include "gemm_core.h"
+
+namespace cce {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kGRowBytes = 256 * 2 + 16;     // LDS staging row of a G tile (256 bf16 + pad)
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Workgroup id -> linear work index such that workgroups resident on one XCD (ids that are
+// equal modulo 8 are dispatched to the same XCD) receive consecutive work indices.
+__device__ __forceinline__ int xcd_linear_id(int bid, int nb) {
+    const int q = nb >> 3, r = nb & 7;
+    const int x = bid & 7, slot = bid >> 3;
+    return x * q + (x < r ? x : r) + slot;
+}
+
+// Merge two (max, sum) pairs kept in the log2 domain; safe for empty pairs (m = -inf, d = 0).
+__device__ __forceinline__ void md_merge(float& m, float& d, float m2, float d2) {
+    const float mn = fmaxf(m, m2);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;
+    d = d * fast_exp2(m - ms) + d2 * fast_exp2(m2 - ms);
+    m = mn;
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward: per (token tile, vocabulary split) online log-sum-exp.
+// Tile orientation: M = vocabulary (A = W, K-major), N = tokens (B = H, K-major), so that in
+// the 32x32 accumulator layout a lane owns ONE token column and 16 vocabulary rows of each
+// block: the running max / sum of a token is lane-local until the very end.
+// partials[token * S + split] = (m, d) with m in the log2 domain (m = max_v z * log2 e).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void lse_partial_kernel(
+        const void* __restrict__ H, const void* __restrict__ W,
+        int N, int D, int V, int TT, int VT, int S, float2* __restrict__ partials) {
+    typedef TileBig Cfg;
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
+
+    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
+    const int s = lin / TT, tt = lin % TT;
+    const int vt0 = (int)((int64_t)s * VT / S), vt1 = (int)((int64_t)(s + 1) * VT / S);
+    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WN;
+
+    OperandTile<true, Cfg::BN> Bop;
+    Bop.init(H, D, tt * Cfg::BN, N, D);
+
+    float run_m[Cfg::TN], run_d[Cfg::TN];
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) { run_m[bn] = -INFINITY; run_d[bn] = 0.f; }
+
+    for (int vt = vt0; vt < vt1; ++vt) {
+        f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+        for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+            for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
+
+        OperandTile<true, Cfg::BM> Aop;
+        Aop.init(W, D, vt * Cfg::BM, V, D);
+        gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+
+        if ((vt + 1) * Cfg::BM > V) {       // ragged last vocabulary tile: mask rows >= V
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const bool dead = vt * Cfg::BM + acc_row<Cfg>(bm, r) >= V;
+#pragma unroll
+                    for (int bn = 0; bn < Cfg::TN; ++bn)
+                        acc[bm][bn][r] = dead ? -INFINITY : acc[bm][bn][r];
+                }
+        }
+#pragma unroll
+        for (int bn = 0; bn < Cfg::TN; ++bn) {
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[bm][bn][r]);
+            const float mn = fmaxf(run_m[bn], tmax * kLog2e);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[bm][bn][r], kLog2e, -ms));
+            run_d[bn] = run_d[bn] * fast_exp2(run_m[bn] - ms) + sum;
+            run_m[bn] = mn;
+        }
+    }
+
+    // lanes l and l ^ 32 hold the same token column (different vocabulary rows)
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        const float om = __shfl_xor(run_m[bn], 32), od = __shfl_xor(run_d[bn], 32);
+        md_merge(run_m[bn], run_d[bn], om, od);
+    }
+    // the WM waves stacked along the vocabulary dimension share token columns: merge via LDS
+    CCE_LDS f32x2* red = (CCE_LDS f32x2*)smem;        // [WM][BN]
+    if (l < 32) {
+#pragma unroll
+        for (int bn = 0; bn < Cfg::TN; ++bn)
+            red[wm * Cfg::BN + acc_col<Cfg>(bn)] = f32x2{run_m[bn], run_d[bn]};
+    }
+    __syncthreads();
+    if (threadIdx.x < Cfg::BN) {
+        const int tok = tt * Cfg::BN + threadIdx.x;
+        float m = -INFINITY, d = 0.f;
+#pragma unroll
+        for (int w = 0; w < Cfg::WM; ++w) {
+            const f32x2 p = red[w * Cfg::BN + threadIdx.x];
+            md_merge(m, d, p.x, p.y);
+        }
+        if (tok < N) partials[(size_t)tok * S + s] = make_float2(m, d);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward finalisation: one wavefront per token.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void finalize_kernel(
+        const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, const int32_t* __restrict__ labels,
+        const float2* __restrict__ partials, int N, int D, int V, int S, int32_t ignore_index,
+        float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status) {
+    const int l = threadIdx.x & 63;
+    const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tok >= N) return;
+    const int32_t y = labels[tok];
+    const bool in_range = (y >= 0 && y < V);
+    if (y == ignore_index || !in_range) {
+        if (l == 0) {
+            loss[tok] = 0.f;
+            lse[tok] = 0.f;
+            if (y != ignore_index) atomicOr(status, CCE_STATUS_BAD_LABEL);
+        }
+        return;
+    }
+    float m = -INFINITY, d = 0.f;
+    for (int i = l; i < S; i += 64) {
+        const float2 p = partials[(size_t)tok * S + i];
+        md_merge(m, d, p.x, p.y);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float om = __shfl_xor(m, o), od = __shfl_xor(d, o);
+        md_merge(m, d, om, od);
+    }
+    // label logit: fp32 dot product of the two bf16 rows
+    const uint16_t* h = H + (size_t)tok * D;
+    const uint16_t* w = W + (size_t)y * D;
+    float zy = 0.f;
+    for (int k = l * 2; k < D; k += 128) {
+        const uint32_t hv = *(const uint32_t*)(h + k), wv = *(const uint32_t*)(w + k);
+        zy = fmaf(__uint_as_float(hv << 16), __uint_as_float(wv << 16), zy);
+        zy = fmaf(__uint_as_float(hv & 0xffff0000u), __uint_as_float(wv & 0xffff0000u), zy);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) zy += __shfl_xor(zy, o);
+    if (l == 0) {
+        const float out = (m + fast_log2(d)) * kLn2;
+        lse[tok] = out;
+        loss[tok] = out - zy;
+    }
+}
+
+__global__ void clear_status_kernel(int32_t* status) { if (threadIdx.x == 0) status[0] = 0; }
+
+// ------------------------------------------------------------------------------------------
+// Backward, step 1: recompute one logit tile and store the bf16 gradient tile
+//   G[i, v] = dloss_i * (exp(z_iv - lse_i) - [v == y_i]),   0 where the row is ignored /
+//   beyond N or the column is beyond V.
+// Same orientation as the forward (lane owns a token column).  The tile is staged in LDS as
+// [token][vocab] and written to the scratch chunk G (row-major [rows_pad][ldg], vocab
+// contiguous) with full 512-byte rows.
+// Grid: one workgroup per tile of the [row block x chunk]; tile index -> (ti, vi).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void grad_tile_kernel(
+        const void* __restrict__ H, const void* __restrict__ W, const int32_t* __restrict__ labels,
+        const float* __restrict__ lse, const float* __restrict__ dloss,
+        int N, int D, int V, int32_t ignore_index,
+        int row0, int n_row_tiles, int v0, int n_v_tiles,
+        uint16_t* __restrict__ G, int ldg) {
+    typedef TileBig Cfg;
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
+    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WN;
+
+    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
+    const int vi = lin / n_row_tiles, ti = lin % n_row_tiles;   // consecutive ids share a W tile
+    const int tok0 = row0 + ti * Cfg::BN;        // first token of the tile (global index)
+    const int vt0 = v0 + vi * Cfg::BM;           // first vocabulary row of the tile (global index)
+
+    f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
+
+    OperandTile<true, Cfg::BM> Aop;
+    OperandTile<true, Cfg::BN> Bop;
+    Aop.init(W, D, vt0, V, D);
+    Bop.init(H, D, tok0, N, D);
+    gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+
+    // epilogue: softmax gradient, bf16, stage to LDS [token][vocab]
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        const int col = acc_col<Cfg>(bn);
+        const int tok = tok0 + col;
+        const bool tok_ok = tok < N;
+        const int32_t y = tok_ok ? labels[tok] : -1;
+        const float dl = tok_ok ? dloss[tok] : 0.f;
+        const float nl2 = tok_ok ? -lse[tok] * kLog2e : 0.f;
+        const int yrel = y - (vt0 + wm * (Cfg::TM * 32));     // label relative to this wave's rows
+        const bool hit = (yrel >= 0) && (yrel < Cfg::TM * 32);
+#pragma unroll
+        for (int bm = 0; bm < Cfg::TM; ++bm) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                float g[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) g[e] = fast_exp2(fmaf(acc[bm][bn][r4 * 4 + e], kLog2e, nl2));
+                const int rrel = bm * 32 + 8 * r4 + 4 * (l >> 5);      // first of 4 consecutive rows
+                if (hit) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) g[e] -= (rrel + e == yrel) ? 1.f : 0.f;
+                }
+                const int vrow = wm * (Cfg::TM * 32) + rrel;            // row inside the tile
+                const int vglob = vt0 + vrow;
+                union { __bf16 h[4]; u32x2 u; } pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)((vglob + e < V) ? g[e] * dl : 0.f);
+                *(CCE_LDS u32x2*)(smem + col * kGRowBytes + vrow * 2) = pk.u;
+            }
+        }
+    }
+    __syncthreads();
+    // coalesced store: thread -> (row = t / 32 + 16 j, 16-byte chunk = t % 32)
+    {
+        const int chunk = threadIdx.x & 31;
+#pragma unroll 4
+        for (int j = 0; j < 16; ++j) {
+            const int row = (threadIdx.x >> 5) + 16 * j;
+            const int tok = tok0 + row;
+            bool live = tok < N;
+            if (live) {
+                const int32_t y = labels[tok];
+                live = (y != ignore_index) && (y >= 0) && (y < V);
+            }
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (live) v = *(const CCE_LDS u32x4*)(smem + row * kGRowBytes + chunk * 16);
+            *(u32x4*)(G + (size_t)(ti * Cfg::BN + row) * ldg + (size_t)vi * Cfg::BM + chunk * 8) = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward, step 2: the two gradient contractions of one [row block x chunk], in ONE launch
+// so that their tiles fill the GPU together.  Both have N = hidden dimension:
+//   dH job (A K-major): C[token, d] = sum_v G[token, v] * W[v, d]
+//   dW job (A K-slow ): C[vocab, d] = sum_i G[i, vocab] * H[i, d]
+// A is the scratch chunk G (zero padded to tile multiples in both directions), B is a slice
+// of an input tensor in K-slow layout.  out_f32 (+)= C when `beta`; when out_bf16 is given
+// the sum is rounded to bf16 there instead.  Rows >= m_valid and columns >= n_valid are
+// dropped.  Workgroups [0, dh.n_work) serve the dH job, the rest the dW job.
+// ------------------------------------------------------------------------------------------
+struct GemmJob {
+    const uint16_t* A; int lda; int a_free_n; int a_k_n;
+    const void* B; int ldb; int b_k_n; int k_total;
+    int n_tiles; int n_work; int m_valid; int n_valid;
+    float* out_f32; int64_t ld_out; int beta;
+    uint16_t* out_bf16; int64_t ld_out_bf16;
+};
+
+template <class Cfg, bool A_KMAJOR>
+__device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS char* smem) {
+    const int mi = item / j.n_tiles, ni = item % j.n_tiles;    // consecutive items share the A band
+
+    f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
+
+    OperandTile<A_KMAJOR, Cfg::BM> Aop;
+    OperandTile<false, Cfg::BN> Bop;
+    Aop.init(j.A, j.lda, mi * Cfg::BM, j.a_free_n, j.a_k_n);
+    Bop.init(j.B, j.ldb, ni * Cfg::BN, j.n_valid, j.b_k_n);
+    gemm_mainloop<Cfg, A_KMAJOR, false>(acc, Aop, Bop, j.k_total, smem);
+
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        const int col = ni * Cfg::BN + acc_col<Cfg>(bn);
+        if (col >= j.n_valid) continue;
+#pragma unroll
+        for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = mi * Cfg::BM + acc_row<Cfg>(bm, r);
+                if (row >= j.m_valid) continue;
+                float v = acc[bm][bn][r];
+                float* p = j.out_f32 + (size_t)row * j.ld_out + col;
+                if (j.beta) v += *p;
+                if (j.out_bf16) {
+                    union { __bf16 h; uint16_t u; } cv;
+                    cv.h = (__bf16)v;
+                    j.out_bf16[(size_t)row * j.ld_out_bf16 + col] = cv.u;
+                } else {
+                    *p = v;
+                }
+            }
+    }
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob dh, const GemmJob dw) {
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
+    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
+    if (lin < dh.n_work) run_gemm_job<Cfg, true>(dh, lin, smem);
+    else run_gemm_job<Cfg, false>(dw, lin - dh.n_work, smem);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+static thread_local int g_last_hip_error = 0;
+
+static inline bool hip_ok(hipError_t e) {
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return false; }
+    return true;
+}
+
+static int device_cu_count() {
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    cached = n;
+    return n;
+}
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Plan {
+    int TT, VT, S;              // forward: token tiles, vocabulary tiles, vocabulary splits
+    int64_t Nb, Vc;             // backward: rows per row block, vocabulary columns per chunk (multiples of 256)
+    size_t off_status, off_partials, off_dhacc, off_g, total;
+};
+
+// Workspace budget: 1 % of the materialised fp32 logits, but never below a floor that
+// keeps the backward chunks large enough to fill the GPU.
+static constexpr size_t kBudgetFloor = 48u << 20;
+
+static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
+    if (N <= 0 || D <= 0 || V <= 0) return false;
+    const int cus = device_cu_count();
+    const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
+    p->TT = (int)(Np / 256);
+    p->VT = (int)(Vp / 256);
+    int S = (cus + p->TT - 1) / p->TT;
+    if (S > p->VT) S = p->VT;
+    if (S < 1) S = 1;
+    p->S = S;
+
+    const size_t partial_bytes = (size_t)round_up((int64_t)N * S * 8, 256);
+    size_t budget = (size_t)((double)N * (double)V * 4.0 * 0.01);
+    if (budget < kBudgetFloor) budget = kBudgetFloor;
+    const size_t fixed = 256 + partial_bytes;
+    // choose the row block Nb (256 * 2^j) and chunk Vc minimising the extra accumulate traffic
+    //   (V / Vc) * N * D * 8  [dH accumulator read+write per chunk]  +  (N / Nb) * V * D * 8  [dW]
+    double best_cost = 1e300;
+    int64_t bestNb = 256, bestVc = 256;
+    for (int64_t Nb = 256; ; Nb *= 2) {
+        const int64_t nb = Nb < Np ? Nb : Np;
+        const double acc_bytes = (double)nb * D * 4.0;
+        double room = (double)budget - (double)fixed - acc_bytes;
+        int64_t Vc = room > 0 ? (int64_t)(room / (nb * 2.0)) / 256 * 256 : 0;
+        if (Vc > Vp) Vc = Vp;
+        if (Vc < 256) Vc = 256;
+        const double cost = (double)Vp / Vc * (double)N * D * 8.0 + (double)Np / nb * (double)V * D * 8.0;
+        const bool fits = (double)fixed + acc_bytes + (double)nb * Vc * 2.0 <= (double)budget;
+        if ((fits || nb == 256) && cost < best_cost) { best_cost = cost; bestNb = nb; bestVc = Vc; }
+        if (nb >= Np) break;
+    }
+    p->Nb = bestNb;
+    p->Vc = bestVc;
+    p->off_status = 0;
+    p->off_partials = 256;
+    p->off_dhacc = p->off_partials + partial_bytes;
+    p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 4, 256);
+    p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
+    return true;
+}
+
+static int check_common(const void* hidden, const void* weight, const int32_t* labels,
+                        int64_t N, int64_t D, int64_t V, void* workspace, size_t workspace_bytes, Plan* plan) {
+    if (!hidden || !weight || !labels || !workspace) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || V <= 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (N > (1 << 30) || V > (1 << 30) || V * D * 2 >= ((int64_t)1 << 32) || N * D * 2 >= ((int64_t)1 << 32))
+        return CCE_ERR_UNSUPPORTED;
+    if (((uintptr_t)hidden | (uintptr_t)weight | (uintptr_t)labels) & 15) return CCE_ERR_INVALID;
+    if ((uintptr_t)workspace & 255) return CCE_ERR_INVALID;
+    if (!make_plan(N, D, V, plan)) return CCE_ERR_INVALID;
+    if (workspace_bytes < plan->total) return CCE_ERR_INVALID;
+    return CCE_OK;
+}
+
+template <class K>
+static bool allow_big_lds(K kernel, int bytes) {
+    return hip_ok(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+}
+
+}  // namespace cce
+
+using namespace cce;
+
+extern "C" {
+
+const char* cce_version(void) { return "0.1.0"; }
+
+const char* cce_strerror(int code) {
+    switch (code) {
+        case CCE_OK: return "ok";
+        case CCE_ERR_INVALID: return "invalid argument (null or misaligned pointer, non-positive size, workspace too small)";
+        case CCE_ERR_UNSUPPORTED: return "unsupported shape (D must be a multiple of 64; tensors must stay below 4 GiB of bf16)";
+        case CCE_ERR_HIP: return "HIP runtime error (see cce_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+int cce_last_hip_error(void) { return g_last_hip_error; }
+
+size_t cce_workspace_bytes(int64_t N, int64_t D, int64_t V) {
+    Plan p;
+    if (N <= 0 || D <= 0 || V <= 0 || D % 64 != 0) return 0;
+    if (!make_plan(N, D, V, &p)) return 0;
+    return p.total;
+}
+
+size_t cce_materialised_logit_bytes(int64_t N, int64_t V) {
+    if (N <= 0 || V <= 0) return 0;
+    return (size_t)N * (size_t)V * 4u;
+}
+
+int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
+                int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+    Plan p;
+    if (!loss || !lse) return CCE_ERR_INVALID;
+    if (((uintptr_t)loss | (uintptr_t)lse) & 3) return CCE_ERR_INVALID;
+    int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
+    if (rc != CCE_OK) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)workspace;
+    int32_t* status = (int32_t*)(ws + p.off_status);
+    float2* partials = (float2*)(ws + p.off_partials);
+
+    if (!allow_big_lds(lse_partial_kernel, TileBig::kLdsBytes)) return CCE_ERR_HIP;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    hipLaunchKernelGGL(lse_partial_kernel, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                       hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials);
+    hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
+                       (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials,
+                       (int)N, (int)D, (int)V, p.S, ignore_index, loss, lse, status);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
+                 const float* lse, const float* dloss,
+                 int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                 void* dHidden, float* dW, int accumulate_dW,
+                 void* workspace, size_t workspace_bytes, void* stream_) {
+    Plan p;
+    if (!lse || !dloss || !dHidden || !dW) return CCE_ERR_INVALID;
+    if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
+    int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
+    if (rc != CCE_OK) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)workspace;
+    float* dhacc = (float*)(ws + p.off_dhacc);
+    uint16_t* G = (uint16_t*)(ws + p.off_g);
+
+    const int grad_lds = 256 * kGRowBytes > TileBig::kLdsBytes ? 256 * kGRowBytes : TileBig::kLdsBytes;
+    if (!allow_big_lds(grad_tile_kernel, grad_lds)) return CCE_ERR_HIP;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, TileNarrow::kLdsBytes)) return CCE_ERR_HIP;
+
+    // 256-wide hidden tiles when D divides evenly, else 128-wide ones (D = 896 = 7 x 128)
+    const bool big = (D % 256 == 0);
+    const int bn = big ? TileBig::BN : TileNarrow::BN;
+    const int d_tiles = (int)((D + bn - 1) / bn);
+    for (int64_t r0 = 0; r0 < N; r0 += p.Nb) {
+        const int64_t rows = (N - r0 < p.Nb) ? (N - r0) : p.Nb;            // valid rows in this block
+        const int row_tiles = (int)((rows + 255) / 256);
+        const int64_t nchunks = (V + p.Vc - 1) / p.Vc;
+        for (int64_t c = 0; c < nchunks; ++c) {
+            const int64_t v0 = c * p.Vc;
+            const int64_t cols = (V - v0 < p.Vc) ? (V - v0) : p.Vc;       // valid vocabulary columns
+            const int v_tiles = (int)((cols + 255) / 256);
+            const int ldg = v_tiles * 256;                                  // chunk is stored densely padded
+            // 1. gradient tiles of this [row block x chunk]
+            hipLaunchKernelGGL(grad_tile_kernel, dim3(row_tiles * v_tiles), dim3(kThreads), grad_lds, stream,
+                               hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
+                               (int)r0, row_tiles, (int)v0, v_tiles, G, ldg);
+            const bool last = (c == nchunks - 1);
+            // 2a. dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
+            GemmJob dh;
+            dh.A = G; dh.lda = ldg; dh.a_free_n = row_tiles * 256; dh.a_k_n = ldg;
+            dh.B = (const void*)((const uint16_t*)weight + (size_t)v0 * D); dh.ldb = (int)D; dh.b_k_n = (int)cols;
+            dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = row_tiles * d_tiles;
+            dh.m_valid = (int)rows; dh.n_valid = (int)D;
+            dh.out_f32 = dhacc; dh.ld_out = D; dh.beta = c > 0 ? 1 : 0;
+            dh.out_bf16 = last ? (uint16_t*)dHidden + (size_t)r0 * D : (uint16_t*)nullptr; dh.ld_out_bf16 = D;
+            // 2b. dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
+            GemmJob dw;
+            dw.A = G; dw.lda = ldg; dw.a_free_n = ldg; dw.a_k_n = row_tiles * 256;
+            dw.B = (const void*)((const uint16_t*)hidden + (size_t)r0 * D); dw.ldb = (int)D; dw.b_k_n = (int)rows;
+            dw.k_total = row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = v_tiles * d_tiles;
+            dw.m_valid = (int)cols; dw.n_valid = (int)D;
+            dw.out_f32 = dW + (size_t)v0 * D; dw.ld_out = D; dw.beta = (r0 > 0 || accumulate_dW) ? 1 : 0;
+            dw.out_bf16 = nullptr; dw.ld_out_bf16 = 0;
+            const int work = dh.n_work + dw.n_work;
+            if (big)
+                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), TileBig::kLdsBytes, stream, dh, dw);
+            else
+                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), TileNarrow::kLdsBytes, stream, dh, dw);
+        }
+    }
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_read_status(const void* workspace, void* stream_, int32_t* status_out) {
+    if (!workspace || !status_out) return CCE_ERR_INVALID;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!hip_ok(hipMemcpyAsync(status_out, workspace, sizeof(int32_t), hipMemcpyDeviceToHost, stream))) return CCE_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize(stream))) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+}  // extern "C"

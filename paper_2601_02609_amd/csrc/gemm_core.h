@@ -1,0 +1,231 @@
+// MFMA main loop shared by the four contractions of the fused LM-head + cross-entropy path
+// (logit tile of the chunked forward algorithm, its recomputation in the backward
+// algorithm, and the two gradient products dH = G W and dW = G^T H).
+//
+// One workgroup = 512 threads = 8 wavefronts arranged WM x WN, computing a BM x BN fp32 tile
+// C[m, n] = sum_k A(m, k) * B(n, k) with v_mfma_f32_32x32x16_bf16.  Each wavefront owns
+// TM x TN blocks of 32 x 32 (16 accumulator registers per block and lane).
+//
+// Operands arrive in one of two global layouts:
+//   K-major : element (free f, k) at base[f * ld + k]   (k contiguous)  -- H and W in the
+//             logit products, G in dH
+//   K-slow  : element (k, free f) at base[k * ld + f]   (f contiguous)  -- W in dH, G and H
+//             in dW; fragments are then fetched with the LDS transpose read
+//             (ds_read_b64_tr_b16), so no transposed copy of any tensor is ever made.
+//
+// K is walked in slices of 64.  A slice of both operands is brought straight from global
+// memory into LDS (global_load_lds_dwordx4: 16 B per lane, a wavefront fills 1 KB of
+// consecutive LDS), double buffered: the loads of slice t+1 are issued before the MFMAs of
+// slice t.  Because the LDS side of such a load is fixed (lane * 16 B), the
+// bank-conflict-avoiding swizzle is applied on the global side: the lane that fills
+// physical 16-byte chunk p of a row fetches logical chunk p ^ f(row).
+//   K-major stage: [R rows][128 B]; f(row) = (row >> 1) & 7, so that the 16 lanes served
+//                  per LDS cycle by a ds_read_b128 (16 rows, same logical chunk) cover all
+//                  64 banks.
+//   K-slow  stage: [64 k-rows][2R B]; logical chunk c is stored at c ^ ((k & 3) << 2), so
+//                  that the 4 k-rows x 64 B touched per cycle by a transpose read fall in
+//                  different quarters of the bank space.
+// Rows / columns past the edge of a matrix are clamped to the last valid one (their
+// products are discarded or meet zero padding in the other operand), so the loop has a
+// single code path for full and ragged tiles.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cce {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kBK = 64;           // K slice
+constexpr int kThreads = 512;     // 8 wavefronts
+
+#define CCE_LDS __attribute__((address_space(3)))
+#define CCE_GLOBAL __attribute__((address_space(1)))
+
+template <int WM_, int WN_, int TM_, int TN_>
+struct TileCfg {
+    static_assert(WM_ * WN_ == 8, "eight wavefronts per workgroup");
+    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
+    static constexpr int BM = WM_ * TM_ * 32;
+    static constexpr int BN = WN_ * TN_ * 32;
+    static constexpr int kAStage = BM * kBK * 2;
+    static constexpr int kBStage = BN * kBK * 2;
+    static constexpr int kStage = kAStage + kBStage;
+    static constexpr int kLdsBytes = 2 * kStage;
+};
+typedef TileCfg<2, 4, 4, 2> TileBig;      // 256 x 256, wave tile 128 x 64
+typedef TileCfg<4, 2, 2, 2> TileNarrow;   // 256 x 128, wave tile  64 x 64
+
+__device__ __forceinline__ void load16_to_lds(const char* g, CCE_LDS char* lds_wave_base) {
+    // Lane i's 16 bytes land at lds_wave_base + 16 * i (lds_wave_base is wave-uniform).
+    __builtin_amdgcn_global_load_lds((const CCE_GLOBAL void*)g, (CCE_LDS void*)lds_wave_base, 16, 0, 0);
+}
+
+// One operand (R = 128 or 256 free indices) of one workgroup tile: global -> LDS.
+template <bool KMAJOR, int R>
+struct OperandTile {
+    static constexpr int NL = R / 64;   // 16-byte loads per thread and K slice
+    const char* base;       // matrix base address
+    uint32_t ld_bytes;      // leading dimension in bytes
+    uint32_t off[NL];       // K-major: clamped row offset + swizzled chunk; K-slow: clamped column offset
+    int krow[NL];           // K-slow: k-row inside a slice handled by load i
+    int k_last;             // K-slow: last valid k (rows beyond are clamped to it)
+
+    // free0: first free index of the tile; free_n: number of valid free indices in the matrix
+    // (a multiple of 8, at least 8, for a K-slow operand); k_n: valid K extent.
+    __device__ __forceinline__ void init(const void* p, int64_t ld, int free0, int free_n, int k_n) {
+        base = (const char*)p;
+        ld_bytes = (uint32_t)(ld * 2);
+        k_last = k_n - 1;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        if (KMAJOR) {
+            const int sw = ((lane >> 4) & 3) | ((wave & 1) << 2);
+            const int c = (lane & 7) ^ sw;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                int row = free0 + 64 * i + 8 * wave + (lane >> 3);
+                row = row < free_n ? row : free_n - 1;
+                off[i] = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
+                krow[i] = 0;
+            }
+        } else {
+            constexpr int CR = R / 8;            // 16-byte chunks per k-row
+            constexpr int RPL = 512 / R;         // k-rows per wavefront load
+            const int sub = lane / CR;           // k-row inside the wavefront load
+            const int k3 = (RPL * wave + sub) & 3;
+            const int c = (lane % CR) ^ (k3 << 2);
+            int col = free0 + c * 8;
+            col = col <= free_n - 8 ? col : free_n - 8;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                off[i] = (uint32_t)col * 2u;
+                krow[i] = (wave + 8 * i) * RPL + sub;
+            }
+        }
+    }
+
+    // Issue this thread's loads of the K slice starting at k0 into `stage` (LDS).
+    __device__ __forceinline__ void issue(CCE_LDS char* stage, int k0) const {
+        const int wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const char* g;
+            if (KMAJOR) {
+                g = base + (size_t)(off[i] + (uint32_t)k0 * 2u);
+            } else {
+                int k = k0 + krow[i];
+                k = k < k_last ? k : k_last;
+                g = base + (size_t)((uint32_t)k * ld_bytes + off[i]);
+            }
+            load16_to_lds(g, stage + (wave + 8 * i) * 1024);
+        }
+    }
+};
+
+// Per-lane LDS byte offsets of the MFMA fragments of one operand, relative to its stage.
+template <bool KMAJOR, int R, int NB>
+struct FragAddr {
+    uint32_t a[KMAJOR ? 4 : NB];   // K-major: one per k16 step; K-slow: one per 32-wide block
+
+    // tile_off: first row/column of this wave's sub-tile inside the R-wide tile.
+    __device__ __forceinline__ void init(int tile_off) {
+        const int l = threadIdx.x & 63;
+        if (KMAJOR) {
+            const int row = tile_off + (l & 31);
+            const int s = ((l & 31) >> 1) & 7;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                a[kk] = (uint32_t)(row * 128 + (((2 * kk + (l >> 5)) ^ s) << 4));
+        } else {
+            const int q = l >> 4, jj = l & 15;
+            const int krow = 8 * (q >> 1) + (jj >> 2);
+            const int within = (jj & 1) * 8;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int col = tile_off + b * 32 + 16 * (q & 1) + 4 * (jj & 3);
+                const int pc = (col >> 3) ^ ((jj >> 2) << 2);
+                a[b] = (uint32_t)(krow * (2 * R) + pc * 16 + within);
+            }
+        }
+    }
+
+    // Fragment of 32-wide block b for k16 step kk of the slice held at `op` (LDS):
+    // lane l gets elements (free = block base + l % 32, k = 16 kk + 8 (l / 32) + 0..7).
+    __device__ __forceinline__ bf16x8 load(const CCE_LDS char* op, int b, int kk) const {
+        if (KMAJOR) {
+            return *(const CCE_LDS bf16x8*)(op + a[kk] + b * (32 * 128));
+        } else {
+            const CCE_LDS char* p = op + a[b] + kk * (16 * 2 * R);
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CCE_LDS s16x4*)p);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CCE_LDS s16x4*)(p + 4 * 2 * R));
+            s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+        }
+    }
+};
+
+// acc[bm][bn] += A-tile * B-tile^T over K slices [0, ceil(k_total / 64)).  The operands
+// clamp / meet zero padding so that reads past k_total contribute zero.
+// `smem` must hold Cfg::kLdsBytes.  Ends with a workgroup barrier, after which the LDS may
+// be reused by the caller.
+template <class Cfg, bool A_KMAJOR, bool B_KMAJOR>
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
+                                               const OperandTile<A_KMAJOR, Cfg::BM>& A,
+                                               const OperandTile<B_KMAJOR, Cfg::BN>& B,
+                                               int k_total, CCE_LDS char* smem) {
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    FragAddr<A_KMAJOR, Cfg::BM, Cfg::TM> fa;
+    FragAddr<B_KMAJOR, Cfg::BN, Cfg::TN> fb;
+    fa.init(wm * (Cfg::TM * 32));
+    fb.init(wn * (Cfg::TN * 32));
+
+    const int KT = (k_total + kBK - 1) / kBK;
+    A.issue(smem, 0);
+    B.issue(smem + Cfg::kAStage, 0);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        CCE_LDS char* cur = smem + (kt & 1) * Cfg::kStage;
+        CCE_LDS char* nxt = smem + ((kt + 1) & 1) * Cfg::kStage;
+        if (kt + 1 < KT) {
+            A.issue(nxt, (kt + 1) * kBK);
+            B.issue(nxt + Cfg::kAStage, (kt + 1) * kBK);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 af[Cfg::TM], bfr[Cfg::TN];
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm) af[bm] = fa.load(cur, bm, kk);
+#pragma unroll
+            for (int bn = 0; bn < Cfg::TN; ++bn) bfr[bn] = fb.load(cur + Cfg::kAStage, bn, kk);
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn)
+                    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bm], bfr[bn], acc[bm][bn], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+}
+
+// Tile coordinates of accumulator element acc[bm][bn][r] of the calling lane.
+template <class Cfg>
+__device__ __forceinline__ int acc_row(int bm, int r) {
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+    return (wave / Cfg::WN) * (Cfg::TM * 32) + bm * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+}
+template <class Cfg>
+__device__ __forceinline__ int acc_col(int bn) {
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+    return (wave % Cfg::WN) * (Cfg::TN * 32) + bn * 32 + (l & 31);
+}
+
+}  // namespace cce

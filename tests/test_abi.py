@@ -1,0 +1,53 @@
+"""The C-ABI shared library loads and exports every symbol include/cce.h declares (no GPU needed),
+and its host-only entry points behave as documented."""
+import os
+import re
+
+import pytest
+
+from paper_2601_02609_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not build.is_built():
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cce.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_symbols() == sorted(binding.EXPORTED_SYMBOLS)
+
+
+def test_every_declared_symbol_is_exported(L):
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_host_only_entry_points(L):
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
+    assert L.cce_strerror(0) == b"ok"
+    assert b"multiple of 64" in L.cce_strerror(binding.CCE_ERR_UNSUPPORTED)
+    # the paper's memory equation: 8 x 1024 tokens x 151,936 x 4 bytes = 4.97 GB
+    assert binding.materialised_logit_bytes(8192, 151936) == 8192 * 151936 * 4
+    assert binding.materialised_logit_bytes(0, 5) == 0
+
+
+def test_workspace_is_small_and_independent_of_NV(L):
+    N, D, V = 8192, 896, 151936
+    ws = binding.workspace_bytes(N, D, V)
+    assert 0 < ws <= 0.01 * binding.materialised_logit_bytes(N, V)
+    # invalid shapes
+    assert binding.workspace_bytes(N, 100, V) == 0
+    assert binding.workspace_bytes(0, D, V) == 0
+    # O(N*D + tile): doubling V must not double the workspace beyond the 1 % budget rule
+    for (n, d, v) in [(16384, 2048, 151936), (32768, 3584, 151936)]:
+        assert binding.workspace_bytes(n, d, v) <= 0.01 * binding.materialised_logit_bytes(n, v)
