@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LM-head + cross-entropy hot path on one MI355X.
+
+A step is one cce_forward + cce_backward over one batch of the Qwen2.5-0.5B LM-head
+shape (N = 8192 tokens, D = 896, V = 151936; seeded synthetic inputs, already resident in
+HBM).  Prints ONE JSON line: tokens/s (the metric the benchmark spec names), the MFMA roofline
+of the dominant kernel family measured with HIP events inside the timed steps, and the
+fp64 CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen05b] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+METRIC = "fused linear-CE fwd+bwd tokens/s at N=8192,D=896,V=151936; % bf16 MFMA peak"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="qwen05b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=8192)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards over tokens or vocabulary "
+              "as described in DESIGN.md, but no multi-GPU code is part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2601_02609_amd import binding as B, build, inputs as I
+
+    if not build.is_built():
+        build.build(verbose=False)
+    B.lib()                                   # raises if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    w = I.make_config(args.workload)
+    N, D, V = w.spec.N, w.spec.D, w.spec.V
+    dev = torch.device("cuda:0")
+    H = torch.from_numpy(w.hidden.view(np.int16)).to(dev).view(torch.bfloat16)
+    W = torch.from_numpy(w.weight.view(np.int16)).to(dev).view(torch.bfloat16)
+    y = torch.from_numpy(w.labels).to(dev)
+    dl = torch.from_numpy(w.dloss_mean).to(dev)
+    ws = B.alloc_workspace(N, D, V)
+    loss = torch.empty(N, dtype=torch.float32, device=dev)
+    lse = torch.empty(N, dtype=torch.float32, device=dev)
+    dH = torch.empty(N, D, dtype=torch.bfloat16, device=dev)
+    dW = torch.empty(V, D, dtype=torch.float32, device=dev)
+
+    def step():
+        B.cce_forward(H, W, y, w.spec.ignore_index, workspace=ws, loss=loss, lse=lse)
+        B.cce_backward(H, W, y, lse, dl, w.spec.ignore_index, workspace=ws, d_hidden=dH, d_weight=dW)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, bracketed by synchronisation
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    total_ms = e0.elapsed_time(e1)
+    ms_per_step = total_ms / args.steps
+    tok_s = N * args.steps / (total_ms * 1e-3)
+
+    # the same K steps once more with the library's HIP events around every kernel launch
+    # (same stream): per-family launch durations for the roofline.  Kept out of the region
+    # above because ~150 event pairs per step add a few percent of gaps between launches.
+    B.profile_begin()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    profiled_ms_per_step = e0.elapsed_time(e1) / args.steps
+    fam = B.profile_end()
+
+    # sanity on the outputs of the last step (finite loss, non-zero gradient, bad labels none)
+    n_valid = w.n_valid
+    mean_loss = float(loss.sum().item()) / max(n_valid, 1)
+    grad_norm = float(dW.double().pow(2).sum().sqrt().item())
+    assert np.isfinite(mean_loss) and grad_norm > 0.0 and B.read_status(ws) == 0
+
+    nvd = float(N) * V * D
+    # algorithmic MFMA flops per step of each family (all N rows are processed)
+    fam_flops = {"lse_partial_kernel": 2 * nvd, "grad_tile_kernel": 2 * nvd, "grad_gemm_kernel": 4 * nvd}
+    dom = max(fam, key=lambda k: fam[k][0])
+    dom_ms, dom_launches = fam[dom]
+    achieved = fam_flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
+    executed_tflops = 8 * nvd / (ms_per_step * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+        "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+        "avg_launch_us": round(dom_ms * 1e3 / max(dom_launches, 1), 2),
+        "launches_per_step": dom_launches // max(args.steps, 1),
+        "flops_per_launch": fam_flops[dom] * args.steps / max(dom_launches, 1),
+        "timed": f"second pass of the same {args.steps} steps with HIP events around every launch "
+                 f"({profiled_ms_per_step:.3f} ms/step with events)",
+        "families_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in fam.items()},
+        "families_tflops": {k: round(fam_flops[k] * args.steps / (v[0] * 1e-3) / 1e12, 1) if v[0] > 0 else None
+                            for k, v in fam.items()},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import cce_oracle as O     # baseline leg only; never on the product path
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rows = min(args.cpu_sample_rows, N)
+        t0 = time.perf_counter()
+        O.forward(w.hidden[:rows], w.weight, w.labels[:rows], w.spec.ignore_index)
+        O.backward(w.hidden[:rows], w.weight, w.labels[:rows], w.dloss_mean[:rows], w.spec.ignore_index)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(rows / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"fp64 oracle forward+backward on the first {rows} of {N} rows with the full "
+                         f"V={V} vocabulary ({dt:.1f} s wall)"}
+
+    out = {
+        "metric": METRIC, "value": round(tok_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={N} D={D} V={V}, {w.spec.ignore_frac:.0%} ignore_index, "
+                               f"seed {w.spec.seed}", "n_valid": n_valid},
+        "tflops_executed_8NVD": round(executed_tflops, 1),
+        "tflops_model_6NVD": round(6 * nvd / (ms_per_step * 1e-3) / 1e12, 1),
+        "pct_bf16_mfma_peak": round(100 * executed_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "workspace_bytes": int(ws.numel()),
+        "workspace_pct_of_logits": round(100.0 * ws.numel() / B.materialised_logit_bytes(N, V), 3),
+        "mean_loss": round(mean_loss, 5),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

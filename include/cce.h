@@ -113,6 +113,23 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
                  void* dHidden, float* dW, int accumulate_dW,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (not part of the paper's method): per-kernel-family GPU time from HIP
+ * events recorded on the caller's stream around every launch of the three MFMA kernel
+ * families between cce_profile_begin() and cce_profile_end().  cce_profile_end()
+ * synchronises on the recorded events and fills, per family (CCE_KERNEL_*), the summed
+ * milliseconds and the number of launches; both arrays are HOST arrays of
+ * CCE_KERNEL_FAMILIES entries.  Host-side state only; use from one thread at a time.
+ */
+enum {
+    CCE_KERNEL_LSE_PARTIAL = 0,   /* forward logit tiles + online log-sum-exp            */
+    CCE_KERNEL_GRAD_TILE = 1,     /* backward logit-tile recompute + bf16 gradient tile  */
+    CCE_KERNEL_GRAD_GEMM = 2,     /* backward dH = G W and dW = G^T H contractions        */
+    CCE_KERNEL_FAMILIES = 3
+};
+int cce_profile_begin(void);
+int cce_profile_end(double* ms_out, int64_t* launches_out);
+
 /* Copies the workspace status word (bit set of CCE_STATUS_*) to *status_out (host).
  * Synchronises `stream`.  The word is cleared at the start of every cce_forward. */
 int cce_read_status(const void* workspace, void* stream, int32_t* status_out);

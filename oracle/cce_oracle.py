@@ -42,7 +42,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "widen_bf16", "logits", "forward", "grad_logits", "backward",
+    "widen_bf16", "logits", "forward", "grad_logits", "backward", "dweight_rows",
     "logit_memory_bytes", "chunk_reduction_factor",
 ]
 
@@ -135,6 +135,21 @@ def backward(hidden_bits, weight_bits, labels, dloss, ignore_index=-100, row_blo
         dH[r0:r1] = G @ W
         dW += G.T @ Hb
     return dH, dW
+
+
+def dweight_rows(hidden_bits, weight_bits, labels, dloss, vocab_rows, ignore_index=-100, row_block=1024):
+    """Rows `vocab_rows` of dW:  dW[v, :] = sum_i G[i, v] H[i, :]  (same definition as
+    backward(), restricted to a few vocabulary rows so that it stays affordable at the
+    benchmark's full sizes).  Every token row still sees its full-vocabulary softmax."""
+    N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
+    vocab_rows = np.asarray(vocab_rows, dtype=np.int64)
+    out = np.zeros((vocab_rows.size, D), dtype=np.float64)
+    for r0 in range(0, N, row_block):
+        r1 = min(N, r0 + row_block)
+        G = grad_logits(hidden_bits[r0:r1], weight_bits, np.asarray(labels)[r0:r1],
+                        np.asarray(dloss)[r0:r1], ignore_index)
+        out += G[:, vocab_rows].T @ widen_bf16(hidden_bits[r0:r1])
+    return out
 
 
 def logit_memory_bytes(B: int, N: int, V: int, bytes_per_logit: int = 4) -> int:

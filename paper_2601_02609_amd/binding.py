@@ -23,7 +23,9 @@ CCE_STATUS_BAD_LABEL = 1
 EXPORTED_SYMBOLS = [
     "cce_version", "cce_strerror", "cce_last_hip_error", "cce_workspace_bytes",
     "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
+    "cce_profile_begin", "cce_profile_end",
 ]
+KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
 _lib = None
 
@@ -64,6 +66,10 @@ def lib() -> ctypes.CDLL:
     L.cce_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_read_status.restype = ctypes.c_int
     L.cce_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    L.cce_profile_begin.restype = ctypes.c_int
+    L.cce_profile_begin.argtypes = []
+    L.cce_profile_end.restype = ctypes.c_int
+    L.cce_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     _lib = L
     return L
 
@@ -163,3 +169,20 @@ def read_status(workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = N
     if rc != CCE_OK:
         raise CCEError(rc, "cce_read_status")
     return int(out.value)
+
+
+def profile_begin() -> None:
+    rc = lib().cce_profile_begin()
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_profile_begin")
+
+
+def profile_end() -> dict:
+    """{family name: (milliseconds, launches)} accumulated since profile_begin()."""
+    n = len(KERNEL_FAMILIES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    rc = lib().cce_profile_end(ms, cnt)
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_profile_end")
+    return {KERNEL_FAMILIES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

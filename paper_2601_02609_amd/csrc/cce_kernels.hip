@@ -17,6 +17,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <math.h>
+#include <vector>
 
 #include "../../include/cce.h"
 #include "gemm_core.h"
@@ -363,6 +364,42 @@ static inline bool hip_ok(hipError_t e) {
     return true;
 }
 
+// Optional per-kernel-family timing with HIP events (cce_profile_begin / cce_profile_end).
+// Off by default; when on, every launch of a timed family is bracketed by two events on the
+// caller's stream.  Not thread safe: profile from one host thread at a time.
+struct ProfState {
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    size_t used = 0;
+    struct Span { int fam; size_t e0, e1; };
+    std::vector<Span> spans;
+    size_t take() {
+        if (used == pool.size()) {
+            hipEvent_t e;
+            if (!hip_ok(hipEventCreate(&e))) return (size_t)-1;
+            pool.push_back(e);
+        }
+        return used++;
+    }
+};
+static ProfState g_prof;
+
+struct ProfSpan {
+    int fam; hipStream_t s; size_t e0 = (size_t)-1;
+    ProfSpan(int fam_, hipStream_t s_) : fam(fam_), s(s_) {
+        if (!g_prof.on) return;
+        e0 = g_prof.take();
+        if (e0 != (size_t)-1) (void)hipEventRecord(g_prof.pool[e0], s);
+    }
+    ~ProfSpan() {
+        if (!g_prof.on || e0 == (size_t)-1) return;
+        const size_t e1 = g_prof.take();
+        if (e1 == (size_t)-1) return;
+        (void)hipEventRecord(g_prof.pool[e1], s);
+        g_prof.spans.push_back({fam, e0, e1});
+    }
+};
+
 static int device_cu_count() {
     static int cached = 0;
     if (cached > 0) return cached;
@@ -492,8 +529,11 @@ int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
 
     if (!allow_big_lds(lse_partial_kernel, TileBig::kLdsBytes)) return CCE_ERR_HIP;
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
-    hipLaunchKernelGGL(lse_partial_kernel, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                       hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials);
+    {
+        ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
+        hipLaunchKernelGGL(lse_partial_kernel, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                           hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials);
+    }
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
                        (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials,
                        (int)N, (int)D, (int)V, p.S, ignore_index, loss, lse, status);
@@ -535,9 +575,12 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
             const int v_tiles = (int)((cols + 255) / 256);
             const int ldg = v_tiles * 256;                                  // chunk is stored densely padded
             // 1. gradient tiles of this [row block x chunk]
-            hipLaunchKernelGGL(grad_tile_kernel, dim3(row_tiles * v_tiles), dim3(kThreads), grad_lds, stream,
-                               hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
-                               (int)r0, row_tiles, (int)v0, v_tiles, G, ldg);
+            {
+                ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
+                hipLaunchKernelGGL(grad_tile_kernel, dim3(row_tiles * v_tiles), dim3(kThreads), grad_lds, stream,
+                                   hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
+                                   (int)r0, row_tiles, (int)v0, v_tiles, G, ldg);
+            }
             const bool last = (c == nchunks - 1);
             // 2a. dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
             GemmJob dh;
@@ -556,6 +599,7 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
             dw.out_f32 = dW + (size_t)v0 * D; dw.ld_out = D; dw.beta = (r0 > 0 || accumulate_dW) ? 1 : 0;
             dw.out_bf16 = nullptr; dw.ld_out_bf16 = 0;
             const int work = dh.n_work + dw.n_work;
+            ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
             if (big)
                 hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), TileBig::kLdsBytes, stream, dh, dw);
             else
@@ -563,6 +607,29 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
         }
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_profile_begin(void) {
+    g_prof.on = true;
+    g_prof.used = 0;
+    g_prof.spans.clear();
+    return CCE_OK;
+}
+
+int cce_profile_end(double* ms_out, int64_t* launches_out) {
+    if (!ms_out || !launches_out) return CCE_ERR_INVALID;
+    g_prof.on = false;
+    for (int i = 0; i < CCE_KERNEL_FAMILIES; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+    for (const ProfState::Span& sp : g_prof.spans) {
+        float ms = 0.f;
+        if (!hip_ok(hipEventSynchronize(g_prof.pool[sp.e1]))) return CCE_ERR_HIP;
+        if (!hip_ok(hipEventElapsedTime(&ms, g_prof.pool[sp.e0], g_prof.pool[sp.e1]))) return CCE_ERR_HIP;
+        ms_out[sp.fam] += ms;
+        launches_out[sp.fam] += 1;
+    }
+    g_prof.spans.clear();
+    g_prof.used = 0;
     return CCE_OK;
 }
 

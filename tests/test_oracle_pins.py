@@ -282,6 +282,16 @@ def test_row_blocking_does_not_change_results():
     assert np.array_equal(dHa, dHb) and np.allclose(dWa, dWb, atol=1e-14)
 
 
+def test_dweight_rows_matches_full_backward_and_torch():
+    H, W, y, dl = _small(N=40, D=8, V=50, ignore=(3, 9))
+    _, dW = O.backward(H, W, y, dl, IGN)
+    rows = np.array([0, 7, 49, int(y[0])])
+    got = O.dweight_rows(H, W, y, dl, rows, IGN, row_block=16)
+    assert np.allclose(got, dW[rows], atol=1e-14)
+    _, _, dW_t = _torch_ref(H, W, y, dl)
+    assert np.allclose(got, dW_t[rows], atol=1e-12)
+
+
 def test_widen_bf16_exact():
     vals = np.array([0.0, 1.0, -2.5, 3.140625, 2.0 ** -126, -2.0 ** 100], dtype=np.float32)
     bits = (vals.view(np.uint32) >> 16).astype(np.uint16)     # all exactly representable
