@@ -18,6 +18,7 @@ HIPCC_FLAGS = [
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Wno-inline-asm",          # the M0 clobber of the global->LDS load is intentional
 ]
 
 

@@ -39,6 +39,18 @@ __device__ __forceinline__ int xcd_linear_id(int bid, int nb) {
     return x * q + (x < r ? x : r) + slot;
 }
 
+// Linear index -> (i, j) over an n_i x n_j grid, walking i fastest inside groups of `group`
+// consecutive i, then j, then the next group (the last group may be narrower).
+__device__ __forceinline__ void group_map(int lin, int n_i, int n_j, int group, int& i, int& j) {
+    const int width = group * n_j;
+    const int g = lin / width;
+    const int first = g * group;
+    const int size = (n_i - first < group) ? (n_i - first) : group;
+    const int r = lin - g * width;
+    i = first + r % size;
+    j = r / size;
+}
+
 // Merge two (max, sum) pairs kept in the log2 domain; safe for empty pairs (m = -inf, d = 0).
 __device__ __forceinline__ void md_merge(float& m, float& d, float m2, float d2) {
     const float mn = fmaxf(m, m2);
@@ -61,8 +73,12 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
 
+    // Work index -> (token tile, vocabulary split).  The 32 workgroups that share an XCD (and
+    // its 4 MB L2) take a panel of 4 token tiles x all splits: per K slice they touch 4 H
+    // tiles + S W tiles instead of 32 + 1, which is what keeps most operand fetches in L2.
     const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
-    const int s = lin / TT, tt = lin % TT;
+    int tt, s;
+    group_map(lin, TT, S, 4, tt, s);
     const int vt0 = (int)((int64_t)s * VT / S), vt1 = (int)((int64_t)(s + 1) * VT / S);
     const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WN;
@@ -215,7 +231,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     const int wm = wave / Cfg::WN;
 
     const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
-    const int vi = lin / n_row_tiles, ti = lin % n_row_tiles;   // consecutive ids share a W tile
+    int ti, vi;
+    group_map(lin, n_row_tiles, n_v_tiles, 4, ti, vi);          // an XCD works on ~4 x 8 tiles
     const int tok0 = row0 + ti * Cfg::BN;        // first token of the tile (global index)
     const int vt0 = v0 + vi * Cfg::BM;           // first vocabulary row of the tile (global index)
 
@@ -295,6 +312,15 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 // the sum is rounded to bf16 there instead.  Rows >= m_valid and columns >= n_valid are
 // dropped.  Workgroups [0, dh.n_work) serve the dH job, the rest the dW job.
 // ------------------------------------------------------------------------------------------
+// LDS of grad_gemm_kernel: the main loop's stages or the epilogue staging, whichever is larger.
+constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
+    const int one_pass = bm * (bn + 8) * 4;
+    const int staging = one_pass <= 150 * 1024 ? one_pass : one_pass / 2;
+    return staging > main_loop ? staging : main_loop;
+}
+constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, TileBig::BN);
+constexpr int kGemmLdsNarrow = gemm_lds_bytes(TileNarrow::kLdsBytes, TileNarrow::BM, TileNarrow::BN);
+
 struct GemmJob {
     const uint16_t* A; int lda; int a_free_n; int a_k_n;
     const void* B; int ldb; int b_k_n; int k_total;
@@ -321,27 +347,54 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     Bop.init(j.B, j.ldb, ni * Cfg::BN, j.n_valid, j.b_k_n);
     gemm_mainloop<Cfg, A_KMAJOR, false>(acc, Aop, Bop, j.k_total, smem);
 
+    // Epilogue through LDS so that global memory sees 16-byte accesses along full rows:
+    // the fp32 tile is staged [rows][BN + 8 floats] (the padding keeps the two 128-byte
+    // row segments a wavefront writes per instruction in different halves of the banks),
+    // half of the rows at a time when the whole tile does not fit.
+    constexpr int kPasses = (Cfg::BM * (Cfg::BN + 8) * 4 <= 150 * 1024) ? 1 : 2;
+    constexpr int kRowsPerPass = Cfg::BM / kPasses;
+    constexpr int kRowBytes = (Cfg::BN + 8) * 4;
+    constexpr int kChunksPerRow = Cfg::BN / 4;                 // 16-byte chunks
+    constexpr int kRowsPerIter = kThreads / kChunksPerRow;
+    static_assert(kRowsPerPass * kRowBytes <= 160 * 1024, "epilogue staging must fit the LDS");
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave / Cfg::WN;
+    const int wave_row0 = wm * (Cfg::TM * 32);
 #pragma unroll
-    for (int bn = 0; bn < Cfg::TN; ++bn) {
-        const int col = ni * Cfg::BN + acc_col<Cfg>(bn);
-        if (col >= j.n_valid) continue;
+    for (int pass = 0; pass < kPasses; ++pass) {
+        const int pr0 = pass * kRowsPerPass;
+        if (wave_row0 >= pr0 && wave_row0 < pr0 + kRowsPerPass) {
 #pragma unroll
-        for (int bm = 0; bm < Cfg::TM; ++bm)
+            for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = mi * Cfg::BM + acc_row<Cfg>(bm, r);
+                for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        *(CCE_LDS float*)(smem + (acc_row<Cfg>(bm, r) - pr0) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
+        }
+        __syncthreads();
+        const int chunk = threadIdx.x % kChunksPerRow;
+        const int col = ni * Cfg::BN + chunk * 4;
+        if (col < j.n_valid) {                       // n_valid is a multiple of 8: whole chunks
+#pragma unroll 4
+            for (int it = 0; it < kRowsPerPass / kRowsPerIter; ++it) {
+                const int lrow = it * kRowsPerIter + threadIdx.x / kChunksPerRow;
+                const int row = mi * Cfg::BM + pr0 + lrow;
                 if (row >= j.m_valid) continue;
-                float v = acc[bm][bn][r];
+                f32x4 v = *(const CCE_LDS f32x4*)(smem + lrow * kRowBytes + chunk * 16);
                 float* p = j.out_f32 + (size_t)row * j.ld_out + col;
-                if (j.beta) v += *p;
+                if (j.beta) v += *(const f32x4*)p;
                 if (j.out_bf16) {
-                    union { __bf16 h; uint16_t u; } cv;
-                    cv.h = (__bf16)v;
-                    j.out_bf16[(size_t)row * j.ld_out_bf16 + col] = cv.u;
+                    union { __bf16 h[4]; u32x2 u; } cv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[e];
+                    *(u32x2*)(j.out_bf16 + (size_t)row * j.ld_out_bf16 + col) = cv.u;
                 } else {
-                    *p = v;
+                    *(f32x4*)p = v;
                 }
             }
+        }
+        if (pass + 1 < kPasses) __syncthreads();
     }
 }
 
@@ -558,8 +611,8 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
 
     const int grad_lds = 256 * kGRowBytes > TileBig::kLdsBytes ? 256 * kGRowBytes : TileBig::kLdsBytes;
     if (!allow_big_lds(grad_tile_kernel, grad_lds)) return CCE_ERR_HIP;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, TileNarrow::kLdsBytes)) return CCE_ERR_HIP;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return CCE_ERR_HIP;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return CCE_ERR_HIP;
 
     // 256-wide hidden tiles when D divides evenly, else 128-wide ones (D = 896 = 7 x 128)
     const bool big = (D % 256 == 0);
@@ -601,9 +654,9 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
             const int work = dh.n_work + dw.n_work;
             ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
             if (big)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), TileBig::kLdsBytes, stream, dh, dw);
+                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, dh, dw);
             else
-                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), TileNarrow::kLdsBytes, stream, dh, dw);
+                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, dh, dw);
         }
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;

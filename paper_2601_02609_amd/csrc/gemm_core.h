@@ -40,6 +40,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
@@ -49,23 +50,33 @@ constexpr int kThreads = 512;     // 8 wavefronts
 #define CCE_LDS __attribute__((address_space(3)))
 #define CCE_GLOBAL __attribute__((address_space(1)))
 
-template <int WM_, int WN_, int TM_, int TN_>
+template <int WM_, int WN_, int TM_, int TN_, int STAGES_>
 struct TileCfg {
     static_assert(WM_ * WN_ == 8, "eight wavefronts per workgroup");
-    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
+    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, STAGES = STAGES_;
     static constexpr int BM = WM_ * TM_ * 32;
     static constexpr int BN = WN_ * TN_ * 32;
     static constexpr int kAStage = BM * kBK * 2;
     static constexpr int kBStage = BN * kBK * 2;
     static constexpr int kStage = kAStage + kBStage;
-    static constexpr int kLdsBytes = 2 * kStage;
+    static constexpr int kLdsBytes = STAGES_ * kStage;
+    static constexpr int kLoadsPerSlice = BM / 64 + BN / 64;   // 16-byte loads per thread
+    static_assert(kLdsBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
 };
-typedef TileCfg<2, 4, 4, 2> TileBig;      // 256 x 256, wave tile 128 x 64
-typedef TileCfg<4, 2, 2, 2> TileNarrow;   // 256 x 128, wave tile  64 x 64
+typedef TileCfg<2, 4, 4, 2, 2> TileBig;      // 256 x 256, wave tile 128 x 64, 2 x 64 KB stages
+typedef TileCfg<4, 2, 2, 2, 3> TileNarrow;   // 256 x 128, wave tile  64 x 64, 3 x 48 KB stages
 
 __device__ __forceinline__ void load16_to_lds(const char* g, CCE_LDS char* lds_wave_base) {
-    // Lane i's 16 bytes land at lds_wave_base + 16 * i (lds_wave_base is wave-uniform).
-    __builtin_amdgcn_global_load_lds((const CCE_GLOBAL void*)g, (CCE_LDS void*)lds_wave_base, 16, 0, 0);
+    // global_load_lds_dwordx4: lane i's 16 bytes land at lds_wave_base + 16 * i
+    // (lds_wave_base is wave-uniform and travels in M0).
+    // Written as inline assembly on purpose: when the compiler sees this load it makes
+    // every later LDS read it cannot disambiguate (the transpose reads in particular) wait
+    // for ALL outstanding global->LDS loads (s_waitcnt vmcnt(0)), which serialises the
+    // prefetch of the next K slice with the current one.  The main loop orders these
+    // loads against the LDS reads itself (barrier_pending_loads).
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(g), "s"(m0) : "memory", "m0");
 }
 
 // One operand (R = 128 or 256 free indices) of one workgroup tile: global -> LDS.
@@ -171,15 +182,51 @@ struct FragAddr {
     }
 };
 
+// Scheduling hint: one MFMA, then PER LDS reads, repeated (compile-time recursion because
+// the builtin wants constant arguments).
+template <int I, int N_MFMA, int N_READS, int PER>
+struct SchedInterleave {
+    static __device__ __forceinline__ void run() {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (I * PER < N_READS)
+            __builtin_amdgcn_sched_group_barrier(0x100, ((I + 1) * PER <= N_READS ? PER : N_READS - I * PER), 0);
+        if constexpr (I + 1 < N_MFMA) SchedInterleave<I + 1, N_MFMA, N_READS, PER>::run();
+    }
+};
+
+// Workgroup barrier that first waits until at most `PENDING` of this thread's global->LDS
+// loads are still in flight and all of its LDS reads have returned.  (__syncthreads would
+// wait for every outstanding load, which defeats a prefetch distance of more than one
+// slice.)  The "memory" clobber keeps the compiler from moving LDS accesses across it.
+template <int PENDING>
+__device__ __forceinline__ void barrier_pending_loads() {
+    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt is a 6-bit counter");
+    if constexpr (PENDING == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(PENDING) : "memory");
+}
+
 // acc[bm][bn] += A-tile * B-tile^T over K slices [0, ceil(k_total / 64)).  The operands
 // clamp / meet zero padding so that reads past k_total contribute zero.
 // `smem` must hold Cfg::kLdsBytes.  Ends with a workgroup barrier, after which the LDS may
 // be reused by the caller.
+//
+// Software pipeline.  Global -> LDS runs STAGES - 1 K slices ahead (STAGES LDS stages; a
+// slice of a 256 x 128 tile lasts only ~0.5 us, less than a trip to L2 / HBM, hence three
+// stages there).  LDS -> registers runs one k16 step ahead (two fragment sets): while the
+// MFMAs of step kk run, the fragments of step kk + 1 are already being read.  The one
+// workgroup barrier per slice sits between the MFMAs of steps 2 and 3: by then every
+// wavefront has issued (and waited for) all its LDS reads of the current stage, so after
+// the barrier (a) the next slice's data, whose loads each wavefront has waited for, is
+// visible to all and its first fragments can be read under the MFMAs of step 3, and (b)
+// the current stage may be overwritten by the loads issued at the top of the next
+// iteration.
 template <class Cfg, bool A_KMAJOR, bool B_KMAJOR>
 __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                                                const OperandTile<A_KMAJOR, Cfg::BM>& A,
                                                const OperandTile<B_KMAJOR, Cfg::BN>& B,
                                                int k_total, CCE_LDS char* smem) {
+    constexpr int S = Cfg::STAGES;
+    constexpr int kAhead = (S - 2) * Cfg::kLoadsPerSlice;    // loads that may stay in flight
     const int wave = threadIdx.x >> 6;
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     FragAddr<A_KMAJOR, Cfg::BM, Cfg::TM> fa;
@@ -188,32 +235,82 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     fb.init(wn * (Cfg::TN * 32));
 
     const int KT = (k_total + kBK - 1) / kBK;
-    A.issue(smem, 0);
-    B.issue(smem + Cfg::kAStage, 0);
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) {
+        if (s < KT) {
+            A.issue(smem + s * Cfg::kStage, s * kBK);
+            B.issue(smem + s * Cfg::kStage + Cfg::kAStage, s * kBK);
+        }
+    }
+    if (KT >= S - 1) barrier_pending_loads<kAhead>();
+    else barrier_pending_loads<0>();
 
+    bf16x8 af[2][Cfg::TM], bfr[2][Cfg::TN];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm) af[0][bm] = fa.load(smem, bm, 0);
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) bfr[0][bn] = fb.load(smem + Cfg::kAStage, bn, 0);
+
+    int cur_s = 0;                       // stage holding slice kt
     for (int kt = 0; kt < KT; ++kt) {
-        CCE_LDS char* cur = smem + (kt & 1) * Cfg::kStage;
-        CCE_LDS char* nxt = smem + ((kt + 1) & 1) * Cfg::kStage;
-        if (kt + 1 < KT) {
-            A.issue(nxt, (kt + 1) * kBK);
-            B.issue(nxt + Cfg::kAStage, (kt + 1) * kBK);
+        CCE_LDS char* cur = smem + cur_s * Cfg::kStage;
+        const int nxt_s = (cur_s + 1 == S) ? 0 : cur_s + 1;
+        CCE_LDS char* nxt = smem + nxt_s * Cfg::kStage;
+#ifdef CCE_DBG_SKIP_GLOBAL
+        const bool more = false;
+#else
+        const bool more = kt + S - 1 < KT;
+#endif
+        if (more) {
+            const int ld_s = (cur_s == 0) ? S - 1 : cur_s - 1;   // stage of slice kt - 1, free again
+            A.issue(smem + ld_s * Cfg::kStage, (kt + S - 1) * kBK);
+            B.issue(smem + ld_s * Cfg::kStage + Cfg::kAStage, (kt + S - 1) * kBK);
         }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 af[Cfg::TM], bfr[Cfg::TN];
+            const int c = kk & 1, n = c ^ 1;
+#ifdef CCE_DBG_SKIP_LDS
+            if (false) {
+#else
+            if (kk < 3) {
+#endif
 #pragma unroll
-            for (int bm = 0; bm < Cfg::TM; ++bm) af[bm] = fa.load(cur, bm, kk);
+                for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = fa.load(cur, bm, kk + 1);
 #pragma unroll
-            for (int bn = 0; bn < Cfg::TN; ++bn) bfr[bn] = fb.load(cur + Cfg::kAStage, bn, kk);
+                for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = fb.load(cur + Cfg::kAStage, bn, kk + 1);
+            } else {
+                // slice kt + 1 must have landed; younger slices may still be in flight
+#ifndef CCE_DBG_SKIP_BARRIER
+                if (more) barrier_pending_loads<kAhead>();
+                else barrier_pending_loads<0>();
+#endif
+#ifndef CCE_DBG_SKIP_LDS
+#pragma unroll
+                for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = fa.load(nxt, bm, 0);
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = fb.load(nxt + Cfg::kAStage, bn, 0);
+#else
+#pragma unroll
+                for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = af[c][bm];
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = bfr[c][bn];
+#endif
+            }
 #pragma unroll
             for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
                 for (int bn = 0; bn < Cfg::TN; ++bn)
-                    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bm], bfr[bn], acc[bm][bn], 0, 0, 0);
+                    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][bm], bfr[c][bn], acc[bm][bn], 0, 0, 0);
+            // issue order for the scheduler: the LDS reads of the next step are spread
+            // one (or two) at a time behind the first MFMAs of this step
+            constexpr int kReads = Cfg::TM * (A_KMAJOR ? 1 : 2) + Cfg::TN * (B_KMAJOR ? 1 : 2);
+            constexpr int kMfma = Cfg::TM * Cfg::TN;
+            constexpr int kPer = (kReads + kMfma - 1) / kMfma;
+            SchedInterleave<0, kMfma, kReads, kPer>::run();
         }
-        __syncthreads();
+        cur_s = nxt_s;
     }
+    barrier_pending_loads<0>();
 }
 
 // Tile coordinates of accumulator element acc[bm][bn][r] of the calling lane.
