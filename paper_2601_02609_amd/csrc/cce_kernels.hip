@@ -80,8 +80,8 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     int tt, s;
     group_map(lin, TT, S, 4, tt, s);
     const int vt0 = (int)((int64_t)s * VT / S), vt1 = (int)((int64_t)(s + 1) * VT / S);
-    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / Cfg::WN;
+    const int l = threadIdx.x & 63;
+    const int wm = wave_m<Cfg>();
 
     OperandTile<true, Cfg::BN> Bop;
     Bop.init(H, D, tt * Cfg::BN, N, D);
@@ -227,8 +227,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
-    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / Cfg::WN;
+    const int l = threadIdx.x & 63;
+    const int wm = wave_m<Cfg>();
 
     const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
     int ti, vi;
@@ -357,13 +357,36 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     constexpr int kChunksPerRow = Cfg::BN / 4;                 // 16-byte chunks
     constexpr int kRowsPerIter = kThreads / kChunksPerRow;
     static_assert(kRowsPerPass * kRowBytes <= 160 * 1024, "epilogue staging must fit the LDS");
-    const int wave = threadIdx.x >> 6;
-    const int wm = wave / Cfg::WN;
-    const int wave_row0 = wm * (Cfg::TM * 32);
+    const int wave_row0 = wave_m<Cfg>() * (Cfg::TM * 32);
+    static_assert(Cfg::KG == 1 || kPasses == 1, "K-group reduction shares the one-pass staging");
+    if (Cfg::KG == 2) {
+        // the two K groups hold partial sums of the same positions: group 1 parks its
+        // accumulators in the staging area, group 0 adds them to its own
+        if (wave_kg<Cfg>() == 1) {
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        *(CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
+        }
+        __syncthreads();
+        if (wave_kg<Cfg>() == 0) {
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[bm][bn][r] += *(const CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4);
+        }
+        // group 0 overwrites exactly the words it has just read, so no barrier is needed here
+    }
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) {
         const int pr0 = pass * kRowsPerPass;
-        if (wave_row0 >= pr0 && wave_row0 < pr0 + kRowsPerPass) {
+        if (wave_kg<Cfg>() == 0 && wave_row0 >= pr0 && wave_row0 < pr0 + kRowsPerPass) {
 #pragma unroll
             for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll

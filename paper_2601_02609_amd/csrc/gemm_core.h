@@ -50,10 +50,16 @@ constexpr int kThreads = 512;     // 8 wavefronts
 #define CCE_LDS __attribute__((address_space(3)))
 #define CCE_GLOBAL __attribute__((address_space(1)))
 
-template <int WM_, int WN_, int TM_, int TN_, int STAGES_>
+// KG_ > 1 splits the k16 steps of every slice between KG_ groups of wavefronts that all work
+// on the same output positions (their accumulators are summed once, after the loop): a
+// 256 x 128 tile then keeps the 128 x 64 wavefront tile of the 256 x 256 one, i.e. 0.75
+// instead of 1 LDS fragment read per MFMA and 8 instead of 4 independent accumulators.
+template <int WM_, int WN_, int TM_, int TN_, int STAGES_, int KG_ = 1>
 struct TileCfg {
-    static_assert(WM_ * WN_ == 8, "eight wavefronts per workgroup");
-    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, STAGES = STAGES_;
+    static_assert(WM_ * WN_ * KG_ == 8, "eight wavefronts per workgroup");
+    static_assert(KG_ == 1 || KG_ == 2, "one or two K groups");
+    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_, STAGES = STAGES_, KG = KG_;
+    static constexpr int kSteps = 4 / KG_;                      // k16 steps per slice and wavefront
     static constexpr int BM = WM_ * TM_ * 32;
     static constexpr int BN = WN_ * TN_ * 32;
     static constexpr int kAStage = BM * kBK * 2;
@@ -64,7 +70,12 @@ struct TileCfg {
     static_assert(kLdsBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
 };
 typedef TileCfg<2, 4, 4, 2, 2> TileBig;      // 256 x 256, wave tile 128 x 64, 2 x 64 KB stages
-typedef TileCfg<4, 2, 2, 2, 3> TileNarrow;   // 256 x 128, wave tile  64 x 64, 3 x 48 KB stages
+typedef TileCfg<2, 2, 4, 2, 3, 2> TileNarrow; // 256 x 128, wave tile 128 x 64, 2 K groups, 3 x 48 KB stages
+
+// Wavefront coordinates inside the workgroup: K group, then position along M and N.
+template <class Cfg> __device__ __forceinline__ int wave_kg() { return (threadIdx.x >> 6) / (Cfg::WM * Cfg::WN); }
+template <class Cfg> __device__ __forceinline__ int wave_m() { return ((threadIdx.x >> 6) % (Cfg::WM * Cfg::WN)) / Cfg::WN; }
+template <class Cfg> __device__ __forceinline__ int wave_n() { return ((threadIdx.x >> 6) % (Cfg::WM * Cfg::WN)) % Cfg::WN; }
 
 __device__ __forceinline__ void load16_to_lds(const char* g, CCE_LDS char* lds_wave_base) {
     // global_load_lds_dwordx4: lane i's 16 bytes land at lds_wave_base + 16 * i
@@ -141,22 +152,25 @@ struct OperandTile {
 };
 
 // Per-lane LDS byte offsets of the MFMA fragments of one operand, relative to its stage.
-template <bool KMAJOR, int R, int NB>
+// A wavefront of K group kg reads the k16 steps kk = j * KG + kg, j = 0 .. STEPS - 1.
+template <bool KMAJOR, int R, int NB, int STEPS, int KG>
 struct FragAddr {
-    uint32_t a[KMAJOR ? 4 : NB];   // K-major: one per k16 step; K-slow: one per 32-wide block
+    uint32_t a[KMAJOR ? STEPS : NB];   // K-major: one per step j; K-slow: one per 32-wide block
 
     // tile_off: first row/column of this wave's sub-tile inside the R-wide tile.
-    __device__ __forceinline__ void init(int tile_off) {
+    __device__ __forceinline__ void init(int tile_off, int kg) {
         const int l = threadIdx.x & 63;
         if (KMAJOR) {
             const int row = tile_off + (l & 31);
             const int s = ((l & 31) >> 1) & 7;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                a[kk] = (uint32_t)(row * 128 + (((2 * kk + (l >> 5)) ^ s) << 4));
+            for (int j = 0; j < STEPS; ++j) {
+                const int kk = j * KG + kg;
+                a[j] = (uint32_t)(row * 128 + (((2 * kk + (l >> 5)) ^ s) << 4));
+            }
         } else {
             const int q = l >> 4, jj = l & 15;
-            const int krow = 8 * (q >> 1) + (jj >> 2);
+            const int krow = 16 * kg + 8 * (q >> 1) + (jj >> 2);
             const int within = (jj & 1) * 8;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -167,13 +181,13 @@ struct FragAddr {
         }
     }
 
-    // Fragment of 32-wide block b for k16 step kk of the slice held at `op` (LDS):
+    // Fragment of 32-wide block b for this wave's step j of the slice held at `op` (LDS):
     // lane l gets elements (free = block base + l % 32, k = 16 kk + 8 (l / 32) + 0..7).
-    __device__ __forceinline__ bf16x8 load(const CCE_LDS char* op, int b, int kk) const {
+    __device__ __forceinline__ bf16x8 load(const CCE_LDS char* op, int b, int j) const {
         if (KMAJOR) {
-            return *(const CCE_LDS bf16x8*)(op + a[kk] + b * (32 * 128));
+            return *(const CCE_LDS bf16x8*)(op + a[j] + b * (32 * 128));
         } else {
-            const CCE_LDS char* p = op + a[b] + kk * (16 * 2 * R);
+            const CCE_LDS char* p = op + a[b] + j * (KG * 16 * 2 * R);
             s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CCE_LDS s16x4*)p);
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CCE_LDS s16x4*)(p + 4 * 2 * R));
             s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -214,10 +228,10 @@ __device__ __forceinline__ void barrier_pending_loads() {
 // slice of a 256 x 128 tile lasts only ~0.5 us, less than a trip to L2 / HBM, hence three
 // stages there).  LDS -> registers runs one k16 step ahead (two fragment sets): while the
 // MFMAs of step kk run, the fragments of step kk + 1 are already being read.  The one
-// workgroup barrier per slice sits between the MFMAs of steps 2 and 3: by then every
+// workgroup barrier per slice sits before the MFMAs of a wavefront's last step: by then every
 // wavefront has issued (and waited for) all its LDS reads of the current stage, so after
 // the barrier (a) the next slice's data, whose loads each wavefront has waited for, is
-// visible to all and its first fragments can be read under the MFMAs of step 3, and (b)
+// visible to all and its first fragments can be read under those last MFMAs, and (b)
 // the current stage may be overwritten by the loads issued at the top of the next
 // iteration.
 template <class Cfg, bool A_KMAJOR, bool B_KMAJOR>
@@ -227,12 +241,11 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                                                int k_total, CCE_LDS char* smem) {
     constexpr int S = Cfg::STAGES;
     constexpr int kAhead = (S - 2) * Cfg::kLoadsPerSlice;    // loads that may stay in flight
-    const int wave = threadIdx.x >> 6;
-    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
-    FragAddr<A_KMAJOR, Cfg::BM, Cfg::TM> fa;
-    FragAddr<B_KMAJOR, Cfg::BN, Cfg::TN> fb;
-    fa.init(wm * (Cfg::TM * 32));
-    fb.init(wn * (Cfg::TN * 32));
+    constexpr int SPS = Cfg::kSteps;
+    FragAddr<A_KMAJOR, Cfg::BM, Cfg::TM, SPS, Cfg::KG> fa;
+    FragAddr<B_KMAJOR, Cfg::BN, Cfg::TN, SPS, Cfg::KG> fb;
+    fa.init(wave_m<Cfg>() * (Cfg::TM * 32), wave_kg<Cfg>());
+    fb.init(wave_n<Cfg>() * (Cfg::TN * 32), wave_kg<Cfg>());
 
     const int KT = (k_total + kBK - 1) / kBK;
 #pragma unroll
@@ -267,12 +280,12 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
             B.issue(smem + ld_s * Cfg::kStage + Cfg::kAStage, (kt + S - 1) * kBK);
         }
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < SPS; ++kk) {
             const int c = kk & 1, n = c ^ 1;
 #ifdef CCE_DBG_SKIP_LDS
             if (false) {
 #else
-            if (kk < 3) {
+            if (kk < SPS - 1) {
 #endif
 #pragma unroll
                 for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = fa.load(cur, bm, kk + 1);
@@ -316,13 +329,13 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
 // Tile coordinates of accumulator element acc[bm][bn][r] of the calling lane.
 template <class Cfg>
 __device__ __forceinline__ int acc_row(int bm, int r) {
-    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
-    return (wave / Cfg::WN) * (Cfg::TM * 32) + bm * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    const int l = threadIdx.x & 63;
+    return wave_m<Cfg>() * (Cfg::TM * 32) + bm * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
 }
 template <class Cfg>
 __device__ __forceinline__ int acc_col(int bn) {
-    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
-    return (wave % Cfg::WN) * (Cfg::TN * 32) + bn * 32 + (l & 31);
+    const int l = threadIdx.x & 63;
+    return wave_n<Cfg>() * (Cfg::TN * 32) + bn * 32 + (l & 31);
 }
 
 }  // namespace cce
