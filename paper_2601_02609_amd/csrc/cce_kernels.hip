@@ -244,21 +244,40 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
 
+    // per-token scalars of this lane's columns, and the liveness of the row this thread will
+    // flag, are fetched before the main loop so that their latency hides under it
+    int32_t col_y[Cfg::TN];
+    float col_dl[Cfg::TN], col_nl2[Cfg::TN];
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        const int tok = tok0 + acc_col<Cfg>(bn);
+        const bool tok_ok = tok < N;
+        col_y[bn] = tok_ok ? labels[tok] : -1;
+        col_dl[bn] = tok_ok ? dloss[tok] : 0.f;
+        col_nl2[bn] = tok_ok ? -lse[tok] * kLog2e : 0.f;
+    }
+    bool row_live = false;
+    if (threadIdx.x < Cfg::BN && tok0 + (int)threadIdx.x < N) {
+        const int32_t y = labels[tok0 + threadIdx.x];
+        row_live = (y != ignore_index) && (y >= 0) && (y < V);
+    }
+
     OperandTile<true, Cfg::BM> Aop;
     OperandTile<true, Cfg::BN> Bop;
     Aop.init(W, D, vt0, V, D);
     Bop.init(H, D, tok0, N, D);
     gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
 
+    CCE_LDS unsigned char* live_flags = (CCE_LDS unsigned char*)(smem + 256 * kGRowBytes);
+    if (threadIdx.x < Cfg::BN) live_flags[threadIdx.x] = row_live ? 1 : 0;
+
     // epilogue: softmax gradient, bf16, stage to LDS [token][vocab]
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int col = acc_col<Cfg>(bn);
-        const int tok = tok0 + col;
-        const bool tok_ok = tok < N;
-        const int32_t y = tok_ok ? labels[tok] : -1;
-        const float dl = tok_ok ? dloss[tok] : 0.f;
-        const float nl2 = tok_ok ? -lse[tok] * kLog2e : 0.f;
+        const int32_t y = col_y[bn];
+        const float dl = col_dl[bn];
+        const float nl2 = col_nl2[bn];
         const int yrel = y - (vt0 + wm * (Cfg::TM * 32));     // label relative to this wave's rows
         const bool hit = (yrel >= 0) && (yrel < Cfg::TM * 32);
 #pragma unroll
@@ -289,12 +308,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 #pragma unroll 4
         for (int j = 0; j < 16; ++j) {
             const int row = (threadIdx.x >> 5) + 16 * j;
-            const int tok = tok0 + row;
-            bool live = tok < N;
-            if (live) {
-                const int32_t y = labels[tok];
-                live = (y != ignore_index) && (y >= 0) && (y < V);
-            }
+            const bool live = live_flags[row] != 0;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (live) v = *(const CCE_LDS u32x4*)(smem + row * kGRowBytes + chunk * 16);
             *(u32x4*)(G + (size_t)(ti * Cfg::BN + row) * ldg + (size_t)vi * Cfg::BM + chunk * 8) = v;
@@ -632,7 +646,7 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
     float* dhacc = (float*)(ws + p.off_dhacc);
     uint16_t* G = (uint16_t*)(ws + p.off_g);
 
-    const int grad_lds = 256 * kGRowBytes > TileBig::kLdsBytes ? 256 * kGRowBytes : TileBig::kLdsBytes;
+    const int grad_lds = (256 * kGRowBytes + 256 > TileBig::kLdsBytes) ? 256 * kGRowBytes + 256 : TileBig::kLdsBytes;
     if (!allow_big_lds(grad_tile_kernel, grad_lds)) return CCE_ERR_HIP;
     if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return CCE_ERR_HIP;
     if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return CCE_ERR_HIP;
