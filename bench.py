@@ -24,6 +24,21 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 METRIC = "fused linear-CE fwd+bwd tokens/s at N=8192,D=896,V=151936; % bf16 MFMA peak"
 
 
+def stored_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc summary kept under profiles/
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration), or None.  Counters cannot
+    be read from inside this process, so the figure comes from that separate, committed run."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            t = line.split()
+            if len(t) >= 3 and t[0] == "traffic_bytes_per_launch" and t[1] == kernel:
+                return float(t[2])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +47,9 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen05b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over tokens or vocabulary "
@@ -66,6 +84,13 @@ def main() -> int:
     def step():
         B.cce_forward(H, W, y, w.spec.ignore_index, workspace=ws, loss=loss, lse=lse)
         B.cce_backward(H, W, y, lse, dl, w.spec.ignore_index, workspace=ws, d_hidden=dH, d_weight=dW)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -110,7 +135,8 @@ def main() -> int:
     executed_tflops = 8 * nvd / (ms_per_step * 1e-3) / 1e12
     roofline = {
         "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-        "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+        "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+        "traffic": stored_traffic(args.workload, dom),
         "avg_launch_us": round(dom_ms * 1e3 / max(dom_launches, 1), 2),
         "launches_per_step": dom_launches // max(args.steps, 1),
         "flops_per_launch": fam_flops[dom] * args.steps / max(dom_launches, 1),

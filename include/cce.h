@@ -26,7 +26,9 @@
  *   - D must be a positive multiple of 64 (the K granule of the MFMA main loop);
  *     N, V >= 1 are otherwise arbitrary (ragged tiles are masked).
  *   - A row whose label equals `ignore_index` yields loss = lse = 0, a zero dHidden
- *     row and no contribution to dW, whatever hidden/dloss hold for it.  A label
+ *     row and no contribution to dW; its dloss entry is never used (it may be NaN or
+ *     Inf) and its hidden row may hold any FINITE values (as in any dense formulation
+ *     of dW = G^T H, a NaN/Inf there would meet the row's zero gradient).  A label
  *     outside [0, V) that is not `ignore_index` is treated the same way and sets
  *     CCE_STATUS_BAD_LABEL in the workspace status word (see cce_read_status).
  *   - Every call returns CCE_OK (0) or a negative error code; nothing throws or
