@@ -22,6 +22,16 @@ What it computes, and where the paper defines it:
                    (chunk-level backward algorithm of the CCE section, summed
                    over all chunks)
 
+Loss variants (same section of the paper as the cross-entropy definition):
+* label smoothing  L_smooth = (1 - eps) L + eps L_uniform,  L_uniform = -(1/V) sum_v z_v + lse
+                   (smoothed cross-entropy definition); its logit gradient is
+                   softmax - (1 - eps) onehot - eps / V
+* z-loss           L_total = L + lambda_z lse^2 (z-loss definition), gradient contribution
+                   2 lambda_z lse softmax (z-loss gradient proposition)
+* mean reduction   sum of the per-token losses over the number of non-ignored rows (the
+                   materialising cross-entropy kernel of the paper divides by n_non_ignore)
+Both variants are per token and combine as (1 - eps) L + eps L_uniform + lambda_z lse^2.
+
 Readings taken where the paper is silent (each is listed in the design notes):
 rows whose label equals ``ignore_index`` give loss 0, lse 0 and contribute
 exactly nothing to either gradient whatever their ``dloss`` holds (the forward
@@ -42,7 +52,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "widen_bf16", "logits", "forward", "grad_logits", "backward", "dweight_rows",
+    "widen_bf16", "logits", "forward", "grad_logits", "backward", "dweight_rows", "mean_loss",
     "logit_memory_bytes", "chunk_reduction_factor",
 ]
 
@@ -83,9 +93,11 @@ def _lse_rows(Z: np.ndarray) -> np.ndarray:
     return m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
 
 
-def forward(hidden_bits, weight_bits, labels, ignore_index=-100, row_block=1024):
+def forward(hidden_bits, weight_bits, labels, ignore_index=-100, row_block=1024,
+            label_smoothing=0.0, z_loss=0.0):
     """Per-token loss and log-sum-exp, float64 [N] each.
 
+    loss_i = (1 - eps) (lse_i - z_iy) + eps (lse_i - mean_v z_iv) + lambda_z lse_i^2.
     Ignored rows: loss = lse = 0 exactly.
     """
     N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
@@ -100,13 +112,17 @@ def forward(hidden_bits, weight_bits, labels, ignore_index=-100, row_block=1024)
         idx = np.nonzero(vb)[0]
         zy = Z[idx, labels[r0:r1][idx]]
         lse[r0 + idx] = l[idx]
-        loss[r0 + idx] = l[idx] - zy
+        ce = l[idx] - zy
+        uniform = l[idx] - Z[idx].mean(axis=1)
+        loss[r0 + idx] = (1.0 - label_smoothing) * ce + label_smoothing * uniform + z_loss * l[idx] ** 2
     return loss, lse
 
 
-def grad_logits(hidden_bits, weight_bits, labels, dloss, ignore_index=-100):
-    """G[i, v] = dloss_i * (softmax(Z_i)_v - 1[v = y_i]); zero rows where ignored.
+def grad_logits(hidden_bits, weight_bits, labels, dloss, ignore_index=-100,
+                label_smoothing=0.0, z_loss=0.0):
+    """G[i, v] = dloss_i * dloss_i/dz_iv; zero rows where ignored.
 
+    d loss_i / d z_iv = softmax_v - (1 - eps) 1[v = y_i] - eps / V + 2 lambda_z lse_i softmax_v.
     Materialises [N x V]: for small inputs or row subsets.
     """
     N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
@@ -114,14 +130,19 @@ def grad_logits(hidden_bits, weight_bits, labels, dloss, ignore_index=-100):
     l = _lse_rows(Z)
     P = np.exp(Z - l[:, None])
     idx = np.nonzero(valid)[0]
-    P[idx, np.asarray(labels)[idx]] -= 1.0
+    if z_loss != 0.0:
+        P = P + (2.0 * z_loss) * l[:, None] * P
+    if label_smoothing != 0.0:
+        P = P - label_smoothing / V
+    P[idx, np.asarray(labels)[idx]] -= (1.0 - label_smoothing)
     g = np.where(valid, np.asarray(dloss, dtype=np.float64), 0.0)   # select, not multiply
     G = P * g[:, None]
     G[~valid] = 0.0
     return G
 
 
-def backward(hidden_bits, weight_bits, labels, dloss, ignore_index=-100, row_block=1024):
+def backward(hidden_bits, weight_bits, labels, dloss, ignore_index=-100, row_block=1024,
+             label_smoothing=0.0, z_loss=0.0):
     """dH [N, D] and dW [V, D] in float64 for upstream per-token gradient dloss [N]."""
     N, D, V, valid = _check(hidden_bits, weight_bits, labels, ignore_index)
     W = widen_bf16(weight_bits)
@@ -131,13 +152,14 @@ def backward(hidden_bits, weight_bits, labels, dloss, ignore_index=-100, row_blo
         r1 = min(N, r0 + row_block)
         Hb = widen_bf16(hidden_bits[r0:r1])
         G = grad_logits(hidden_bits[r0:r1], weight_bits, np.asarray(labels)[r0:r1],
-                        np.asarray(dloss)[r0:r1], ignore_index)
+                        np.asarray(dloss)[r0:r1], ignore_index, label_smoothing, z_loss)
         dH[r0:r1] = G @ W
         dW += G.T @ Hb
     return dH, dW
 
 
-def dweight_rows(hidden_bits, weight_bits, labels, dloss, vocab_rows, ignore_index=-100, row_block=1024):
+def dweight_rows(hidden_bits, weight_bits, labels, dloss, vocab_rows, ignore_index=-100, row_block=1024,
+                 label_smoothing=0.0, z_loss=0.0):
     """Rows `vocab_rows` of dW:  dW[v, :] = sum_i G[i, v] H[i, :]  (same definition as
     backward(), restricted to a few vocabulary rows so that it stays affordable at the
     benchmark's full sizes).  Every token row still sees its full-vocabulary softmax."""
@@ -147,9 +169,16 @@ def dweight_rows(hidden_bits, weight_bits, labels, dloss, vocab_rows, ignore_ind
     for r0 in range(0, N, row_block):
         r1 = min(N, r0 + row_block)
         G = grad_logits(hidden_bits[r0:r1], weight_bits, np.asarray(labels)[r0:r1],
-                        np.asarray(dloss)[r0:r1], ignore_index)
+                        np.asarray(dloss)[r0:r1], ignore_index, label_smoothing, z_loss)
         out += G[:, vocab_rows].T @ widen_bf16(hidden_bits[r0:r1])
     return out
+
+
+def mean_loss(loss, labels, ignore_index=-100):
+    """(mean of the per-token losses over non-ignored rows, their count); mean = 0 if none."""
+    valid = np.asarray(labels) != ignore_index
+    n = int(valid.sum())
+    return (float(np.asarray(loss, dtype=np.float64)[valid].sum() / n) if n else 0.0), n
 
 
 def logit_memory_bytes(B: int, N: int, V: int, bytes_per_logit: int = 4) -> int:

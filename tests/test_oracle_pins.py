@@ -292,6 +292,111 @@ def test_dweight_rows_matches_full_backward_and_torch():
     assert np.allclose(got, dW_t[rows], atol=1e-12)
 
 
+# ---------------------------------------------------------------- loss variants
+
+def _torch_variant(H, W, y, dl, eps, lam):
+    Ht = torch.tensor(I.bf16_bits_to_f32(H), dtype=torch.float64, requires_grad=True)
+    Wt = torch.tensor(I.bf16_bits_to_f32(W), dtype=torch.float64, requires_grad=True)
+    yt = torch.tensor(y.astype(np.int64))
+    Z = Ht @ Wt.T
+    ce = torch.nn.functional.cross_entropy(Z, yt, ignore_index=IGN, reduction="none", label_smoothing=eps)
+    valid = torch.tensor(y != IGN)
+    zl = torch.where(valid, lam * torch.logsumexp(Z, dim=-1) ** 2, torch.zeros((), dtype=torch.float64))
+    loss = ce + zl
+    g = torch.tensor(np.where(y == IGN, 0.0, dl.astype(np.float64)))
+    (loss * g).sum().backward()
+    return loss.detach().numpy(), Ht.grad.numpy(), Wt.grad.numpy()
+
+
+@pytest.mark.parametrize("eps,lam", [(0.1, 0.0), (0.0, 1e-2), (0.2, 3e-3)])
+def test_variants_against_torch_label_smoothing_and_logsumexp(eps, lam):
+    H, W, y, dl = _small(N=21, D=8, V=37, ignore=(0, 11))
+    loss_t, dH_t, dW_t = _torch_variant(H, W, y, dl, eps, lam)
+    loss, lse = O.forward(H, W, y, IGN, label_smoothing=eps, z_loss=lam)
+    dH, dW = O.backward(H, W, y, dl, IGN, row_block=8, label_smoothing=eps, z_loss=lam)
+    assert np.allclose(loss, loss_t, atol=1e-12, rtol=0)
+    assert np.allclose(dH, dH_t, atol=1e-12, rtol=0)
+    assert np.allclose(dW, dW_t, atol=1e-12, rtol=0)
+    rows = np.array([0, 36, int(y[1])])
+    assert np.allclose(O.dweight_rows(H, W, y, dl, rows, IGN, label_smoothing=eps, z_loss=lam), dW_t[rows], atol=1e-12)
+    # lse itself is not affected by the variants
+    assert np.array_equal(lse, O.forward(H, W, y, IGN)[1])
+
+
+def test_variants_closed_form_at_zero_weight():
+    """W = 0: lse = ln V and mean logit 0, so loss = ln V + lambda ln^2 V for any eps; the logit
+    gradient is (1 + 2 lambda ln V)/V - eps/V - (1 - eps) onehot."""
+    V, D, N = 12, 4, 5
+    eps, lam = 0.25, 0.05
+    H = _bits(np.random.default_rng(2).standard_normal((N, D)))
+    W = np.zeros((V, D), dtype=np.uint16)
+    y = np.array([0, 3, 11, IGN, 5], dtype=np.int32)
+    dl = np.full(N, 0.5, dtype=np.float32)
+    loss, _ = O.forward(H, W, y, IGN, label_smoothing=eps, z_loss=lam)
+    lnV = math.log(V)
+    for i in range(N):
+        assert abs(loss[i] - (0.0 if y[i] == IGN else lnV + lam * lnV * lnV)) < 1e-13
+    G = O.grad_logits(H, W, y, dl, IGN, eps, lam)
+    for i in range(N):
+        for v in range(V):
+            want = 0.0 if y[i] == IGN else 0.5 * ((1 + 2 * lam * lnV) / V - eps / V - (1 - eps) * (v == y[i]))
+            assert abs(G[i, v] - want) < 1e-14
+
+
+def test_variant_gradient_row_sums():
+    """Rows of the smoothed gradient still sum to zero; the z-loss adds 2 lambda lse to each row sum."""
+    H, W, y, dl = _small(N=9, D=6, V=20, ignore=(4,))
+    G = O.grad_logits(H, W, y, np.ones(9, np.float32), IGN, label_smoothing=0.3)
+    assert np.all(np.abs(G.sum(axis=1)) < 1e-13)
+    _, lse = O.forward(H, W, y, IGN)
+    G = O.grad_logits(H, W, y, np.ones(9, np.float32), IGN, z_loss=0.01)
+    assert np.allclose(G.sum(axis=1), 2 * 0.01 * lse, atol=1e-13)
+
+
+def test_variant_finite_differences():
+    H, W, y, dl = _small(N=4, D=3, V=6, ignore=(2,))
+    eps, lam = 0.15, 0.02
+    Hf = I.bf16_bits_to_f32(H).astype(np.float64)
+    Wf = I.bf16_bits_to_f32(W).astype(np.float64)
+    g = np.where(y == IGN, 0.0, dl.astype(np.float64))
+
+    def total(Hx, Wx):
+        t = 0.0
+        for i in range(4):
+            if y[i] == IGN:
+                continue
+            z = Wx @ Hx[i]
+            l = math.log(np.exp(z - z.max()).sum()) + z.max()
+            t += g[i] * ((1 - eps) * (l - z[y[i]]) + eps * (l - z.mean()) + lam * l * l)
+        return t
+
+    dH, dW = O.backward(H, W, y, dl, IGN, label_smoothing=eps, z_loss=lam)
+    h = 1e-6
+    for (i, k) in [(0, 0), (1, 2), (3, 1)]:
+        Hp, Hm = Hf.copy(), Hf.copy()
+        Hp[i, k] += h
+        Hm[i, k] -= h
+        assert abs((total(Hp, Wf) - total(Hm, Wf)) / (2 * h) - dH[i, k]) < 1e-8
+    for (v, k) in [(0, 0), (int(y[0]), 1), (5, 2)]:
+        Wp, Wm = Wf.copy(), Wf.copy()
+        Wp[v, k] += h
+        Wm[v, k] -= h
+        assert abs((total(Hf, Wp) - total(Hf, Wm)) / (2 * h) - dW[v, k]) < 1e-8
+
+
+def test_mean_loss_counts_only_valid_rows():
+    loss = np.array([1.0, 0.0, 3.0, 0.0, 5.0])
+    y = np.array([4, IGN, 2, IGN, 0], dtype=np.int32)
+    m, n = O.mean_loss(loss, y, IGN)
+    assert n == 3 and abs(m - 3.0) < 1e-15
+    assert O.mean_loss(np.zeros(2), np.array([IGN, IGN]), IGN) == (0.0, 0)
+    yt = torch.tensor(y.astype(np.int64))
+    Z = torch.randn(5, 6, dtype=torch.float64, generator=torch.Generator().manual_seed(0))
+    per = torch.nn.functional.cross_entropy(Z, yt, ignore_index=IGN, reduction="none").numpy()
+    ref = float(torch.nn.functional.cross_entropy(Z, yt, ignore_index=IGN, reduction="mean"))
+    assert abs(O.mean_loss(per, y, IGN)[0] - ref) < 1e-14
+
+
 def test_widen_bf16_exact():
     vals = np.array([0.0, 1.0, -2.5, 3.140625, 2.0 ** -126, -2.0 ** 100], dtype=np.float32)
     bits = (vals.view(np.uint32) >> 16).astype(np.uint16)     # all exactly representable
