@@ -37,7 +37,7 @@
  *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
  *     O(N*D + tile): per-row partial (max, sum-exp) pairs, an fp32 dHidden
  *     accumulator for one row block and one bf16 [row block x vocab chunk]
- *     gradient tile; it never scales with N*V.  Contents are scratch: nothing
+ *     gradient chunk; it never scales with N*V.  Contents are scratch: nothing
  *     needs to survive between forward and backward except what the caller
  *     passes explicitly (lse).
  */
@@ -114,6 +114,21 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
                  int64_t N, int64_t D, int64_t V, int32_t ignore_index,
                  void* dHidden, float* dW, int accumulate_dW,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning aid: forces the backward tiling to row blocks of `row_tiles` x 256 tokens and
+ * vocabulary chunks of `vocab_tiles` x 256 columns (clamped to the problem size) for all
+ * later calls of this process, cce_workspace_bytes included; (0, 0) restores the automatic
+ * choice, which stays inside the workspace budget (1 % of the materialised logits, at
+ * least 48 MiB).  The chunking is a free parameter of the chunk-level backward
+ * algorithm: results agree across tilings up to fp32 summation order.  Host state only;
+ * not thread safe.  Returns CCE_ERR_INVALID for negative values or when only one is 0.
+ */
+int cce_set_backward_tiling(int row_tiles, int vocab_tiles);
+
+/* The tiling (in 256-wide tiles) the backward uses for this shape: the forced one, else the
+ * automatic choice.  Host only; the two outputs are host ints. */
+int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int* vocab_tiles);
 
 /*
  * Measurement aid (not part of the paper's method): per-kernel-family GPU time from HIP

@@ -23,7 +23,8 @@ CCE_STATUS_BAD_LABEL = 1
 EXPORTED_SYMBOLS = [
     "cce_version", "cce_strerror", "cce_last_hip_error", "cce_workspace_bytes",
     "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
-    "cce_profile_begin", "cce_profile_end",
+    "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
+    "cce_get_backward_tiling",
 ]
 KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
@@ -70,6 +71,10 @@ def lib() -> ctypes.CDLL:
     L.cce_profile_begin.argtypes = []
     L.cce_profile_end.restype = ctypes.c_int
     L.cce_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    L.cce_set_backward_tiling.restype = ctypes.c_int
+    L.cce_set_backward_tiling.argtypes = [ctypes.c_int, ctypes.c_int]
+    L.cce_get_backward_tiling.restype = ctypes.c_int
+    L.cce_get_backward_tiling.argtypes = [i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
     _lib = L
     return L
 
@@ -169,6 +174,22 @@ def read_status(workspace: torch.Tensor, stream: Optional[torch.cuda.Stream] = N
     if rc != CCE_OK:
         raise CCEError(rc, "cce_read_status")
     return int(out.value)
+
+
+def set_backward_tiling(row_tiles: int = 0, vocab_tiles: int = 0) -> None:
+    """Force the backward tiling (in 256-wide tiles); (0, 0) restores the automatic choice."""
+    rc = lib().cce_set_backward_tiling(row_tiles, vocab_tiles)
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_set_backward_tiling")
+
+
+def get_backward_tiling(N: int, D: int, V: int) -> Tuple[int, int]:
+    """(row_tiles, vocab_tiles) of the backward for this shape, in 256-wide tiles."""
+    a, b = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().cce_get_backward_tiling(N, D, V, ctypes.byref(a), ctypes.byref(b))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_get_backward_tiling")
+    return int(a.value), int(b.value)
 
 
 def profile_begin() -> None:

@@ -39,6 +39,17 @@ __device__ __forceinline__ int xcd_linear_id(int bid, int nb) {
     return x * q + (x < r ? x : r) + slot;
 }
 
+// The same for grids larger than the number of workgroups resident at once (one per compute
+// unit): the mapping is applied inside consecutive rounds of `round` workgroup ids (a
+// multiple of 8), so that every XCD receives an equal share of each round instead of one
+// contiguous eighth of the whole grid (which would hand all the early -- longest -- work
+// items to the first XCDs).
+__device__ __forceinline__ int xcd_round_id(int bid, int nb, int round) {
+    const int base = bid - bid % round;
+    const int n = (nb - base < round) ? (nb - base) : round;
+    return base + xcd_linear_id(bid - base, n);
+}
+
 // Linear index -> (i, j) over an n_i x n_j grid, walking i fastest inside groups of `group`
 // consecutive i, then j, then the next group (the last group may be narrower).
 __device__ __forceinline__ void group_map(int lin, int n_i, int n_j, int group, int& i, int& j) {
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     const int l = threadIdx.x & 63;
     const int wm = wave_m<Cfg>();
 
-    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
+    const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
     int ti, vi;
     group_map(lin, n_row_tiles, n_v_tiles, 4, ti, vi);          // an XCD works on ~4 x 8 tiles
     const int tok0 = row0 + ti * Cfg::BN;        // first token of the tile (global index)
@@ -324,7 +335,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 // A is the scratch chunk G (zero padded to tile multiples in both directions), B is a slice
 // of an input tensor in K-slow layout.  out_f32 (+)= C when `beta`; when out_bf16 is given
 // the sum is rounded to bf16 there instead.  Rows >= m_valid and columns >= n_valid are
-// dropped.  Workgroups [0, dh.n_work) serve the dH job, the rest the dW job.
+// dropped.  Workgroups [0, first.n_work) serve the first job, the rest the second; the host
+// puts the job with the longer reduction first so that its tiles are dispatched first.
 // ------------------------------------------------------------------------------------------
 // LDS of grad_gemm_kernel: the main loop's stages or the epilogue staging, whichever is larger.
 constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
@@ -336,6 +348,7 @@ constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, Tile
 constexpr int kGemmLdsNarrow = gemm_lds_bytes(TileNarrow::kLdsBytes, TileNarrow::BM, TileNarrow::BN);
 
 struct GemmJob {
+    int a_kmajor;               // 1: A is K-major (the dH job), 0: A is K-slow (the dW job)
     const uint16_t* A; int lda; int a_free_n; int a_k_n;
     const void* B; int ldb; int b_k_n; int k_total;
     int n_tiles; int n_work; int m_valid; int n_valid;
@@ -369,7 +382,6 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     constexpr int kRowsPerPass = Cfg::BM / kPasses;
     constexpr int kRowBytes = (Cfg::BN + 8) * 4;
     constexpr int kChunksPerRow = Cfg::BN / 4;                 // 16-byte chunks
-    constexpr int kRowsPerIter = kThreads / kChunksPerRow;
     static_assert(kRowsPerPass * kRowBytes <= 160 * 1024, "epilogue staging must fit the LDS");
     const int wave_row0 = wave_m<Cfg>() * (Cfg::TM * 32);
     static_assert(Cfg::KG == 1 || kPasses == 1, "K-group reduction shares the one-pass staging");
@@ -410,25 +422,23 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
                         *(CCE_LDS float*)(smem + (acc_row<Cfg>(bm, r) - pr0) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
         }
         __syncthreads();
-        const int chunk = threadIdx.x % kChunksPerRow;
-        const int col = ni * Cfg::BN + chunk * 4;
-        if (col < j.n_valid) {                       // n_valid is a multiple of 8: whole chunks
+        // thread -> (row, 16-byte chunk) pairs of the staged rows, consecutive threads along a row
 #pragma unroll 4
-            for (int it = 0; it < kRowsPerPass / kRowsPerIter; ++it) {
-                const int lrow = it * kRowsPerIter + threadIdx.x / kChunksPerRow;
-                const int row = mi * Cfg::BM + pr0 + lrow;
-                if (row >= j.m_valid) continue;
-                f32x4 v = *(const CCE_LDS f32x4*)(smem + lrow * kRowBytes + chunk * 16);
-                float* p = j.out_f32 + (size_t)row * j.ld_out + col;
-                if (j.beta) v += *(const f32x4*)p;
-                if (j.out_bf16) {
-                    union { __bf16 h[4]; u32x2 u; } cv;
+        for (int idx = threadIdx.x; idx < kRowsPerPass * kChunksPerRow; idx += kThreads) {
+            const int lrow = idx / kChunksPerRow, chunk = idx % kChunksPerRow;
+            const int col = ni * Cfg::BN + chunk * 4;
+            const int row = mi * Cfg::BM + pr0 + lrow;
+            if (col >= j.n_valid || row >= j.m_valid) continue;      // n_valid is a multiple of 8: whole chunks
+            f32x4 v = *(const CCE_LDS f32x4*)(smem + lrow * kRowBytes + chunk * 16);
+            float* p = j.out_f32 + (size_t)row * j.ld_out + col;
+            if (j.beta) v += *(const f32x4*)p;
+            if (j.out_bf16) {
+                union { __bf16 h[4]; u32x2 u; } cv;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[e];
-                    *(u32x2*)(j.out_bf16 + (size_t)row * j.ld_out_bf16 + col) = cv.u;
-                } else {
-                    *(f32x4*)p = v;
-                }
+                for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[e];
+                *(u32x2*)(j.out_bf16 + (size_t)row * j.ld_out_bf16 + col) = cv.u;
+            } else {
+                *(f32x4*)p = v;
             }
         }
         if (pass + 1 < kPasses) __syncthreads();
@@ -436,12 +446,15 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
 }
 
 template <class Cfg>
-__global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob dh, const GemmJob dw) {
+__global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first, const GemmJob second) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
-    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
-    if (lin < dh.n_work) run_gemm_job<Cfg, true>(dh, lin, smem);
-    else run_gemm_job<Cfg, false>(dw, lin - dh.n_work, smem);
+    const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
+    const bool in_first = lin < first.n_work;
+    const GemmJob& j = in_first ? first : second;
+    const int item = in_first ? lin : lin - first.n_work;
+    if (j.a_kmajor) run_gemm_job<Cfg, true>(j, item, smem);
+    else run_gemm_job<Cfg, false>(j, item, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -512,8 +525,77 @@ struct Plan {
 // keeps the backward chunks large enough to fill the GPU.
 static constexpr size_t kBudgetFloor = 48u << 20;
 
+// Output tile of the two gradient contractions, by hidden size: 256 x 256 when D is a
+// multiple of 256, else 256 x 128 (D = 896 = 7 x 128).  (A 128 x 224 tile, which would give
+// D = 896 exactly 256 equal tiles per 4096 x 4096 chunk, was measured 3 % slower: its
+// 32 x 224 wavefront tiles need 1.14 LDS fragment reads per MFMA instead of 0.75.)
+struct GemmTile { int kind, bm, bn; double us_per_slice; };
+static GemmTile gemm_tile_for(int64_t D) {
+    if (D % 256 == 0) return {0, TileBig::BM, TileBig::BN, 2.0};
+    return {1, TileNarrow::BM, TileNarrow::BN, 1.1};
+}
+
+// Backward tiling forced by cce_set_backward_tiling (0 = automatic).
+static int g_force_row_tiles = 0, g_force_vocab_tiles = 0;
+
+// Rough time model of the backward pipeline, in microseconds, used only to rank tilings.
+// One compute unit runs one workgroup at a time.  Measured on MI355X with random bf16 data:
+// a 256 x 256 x 64 slice of the main loop takes about 2 us, a 256 x 128 x 64 one about 1.1 us;
+// a gradient-tile workgroup adds about 9 us (pipeline fill, softmax epilogue, store of the
+// tile), a contraction workgroup about 4 us.
+struct BackwardModel {
+    int cus; int64_t D; GemmTile tile;
+    double t_tile() const { return (double)(D / 64) * 2.0 + 9.0; }
+    double t_gemm(int k_tiles) const { return (double)(k_tiles * 4) * tile.us_per_slice + 4.0; }
+    int d_tiles() const { return (int)((D + tile.bn - 1) / tile.bn); }
+
+    // Completion time of n1 jobs of length c1 followed by n2 jobs of length c2 <= c1, handed in
+    // that order to `cus` units, each taking the next job when it becomes free.
+    double two_class_makespan(int n1, double c1, int n2, double c2) const {
+        const int full = n1 / cus, rem = n1 % cus;
+        const double tA = full * c1;                 // units without a long job in the last round
+        const double tB = (rem ? full + 1 : full) * c1;
+        if (n2 == 0) return tB;
+        const int nA = cus - rem, nB = rem;
+        // smallest t with nA * floor((t - tA) / c2) + nB * floor((t - tB) / c2) >= n2
+        double best = 1e300;
+        for (int k = 1; k <= n2; ++k) {             // t = tA + k c2
+            const double t = tA + k * c2;
+            const double fromB = t > tB ? (double)(int64_t)((t - tB) / c2) : 0.0;
+            if ((double)nA * k + (double)nB * fromB >= n2) { best = t; break; }
+        }
+        if (nB > 0) {
+            for (int k = 1; k <= n2; ++k) {         // t = tB + k c2
+                const double t = tB + k * c2;
+                if (t >= best) break;
+                const double fromA = (double)(int64_t)((t - tA) / c2);
+                if ((double)nA * fromA + (double)nB * k >= n2) { best = t; break; }
+            }
+        }
+        return best > tB ? best : tB;
+    }
+
+    // One step = the gradient tiles, then the contractions, of an [a x b] block of 256 x 256
+    // tiles: two launches that follow each other on the caller's stream.
+    double step(int a, int b, bool dw_beta) const {
+        const int dt = d_tiles(), per256 = 256 / tile.bm;
+        const int n_dh = a * per256 * dt, n_dw = b * per256 * dt;
+        const double c_dh = t_gemm(b), c_dw = t_gemm(a);
+        const double mk = (c_dh >= c_dw) ? two_class_makespan(n_dh, c_dh, n_dw, c_dw)
+                                          : two_class_makespan(n_dw, c_dw, n_dh, c_dh);
+        // fp32 accumulator traffic of the step at ~3 TB/s
+        const double bytes = (double)a * 256 * D * 8.0 + (dw_beta ? (double)b * 256 * D * 8.0 : (double)b * 256 * D * 4.0);
+        return ((a * b + cus - 1) / cus) * t_tile() + mk + bytes / 3.0e6 + 4.0;
+    }
+};
+
 static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     if (N <= 0 || D <= 0 || V <= 0) return false;
+    struct Key { int64_t N, D, V; int fa, fb; Plan plan; bool valid; };
+    static thread_local Key cache = {0, 0, 0, 0, 0, {}, false};
+    if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.fa == g_force_row_tiles &&
+        cache.fb == g_force_vocab_tiles) { *p = cache.plan; return true; }
+
     const int cus = device_cu_count();
     const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
     p->TT = (int)(Np / 256);
@@ -527,29 +609,42 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     size_t budget = (size_t)((double)N * (double)V * 4.0 * 0.01);
     if (budget < kBudgetFloor) budget = kBudgetFloor;
     const size_t fixed = 256 + partial_bytes;
-    // choose the row block Nb (256 * 2^j) and chunk Vc minimising the extra accumulate traffic
-    //   (V / Vc) * N * D * 8  [dH accumulator read+write per chunk]  +  (N / Nb) * V * D * 8  [dW]
-    double best_cost = 1e300;
-    int64_t bestNb = 256, bestVc = 256;
-    for (int64_t Nb = 256; ; Nb *= 2) {
-        const int64_t nb = Nb < Np ? Nb : Np;
-        const double acc_bytes = (double)nb * D * 4.0;
-        double room = (double)budget - (double)fixed - acc_bytes;
-        int64_t Vc = room > 0 ? (int64_t)(room / (nb * 2.0)) / 256 * 256 : 0;
-        if (Vc > Vp) Vc = Vp;
-        if (Vc < 256) Vc = 256;
-        const double cost = (double)Vp / Vc * (double)N * D * 8.0 + (double)Np / nb * (double)V * D * 8.0;
-        const bool fits = (double)fixed + acc_bytes + (double)nb * Vc * 2.0 <= (double)budget;
-        if ((fits || nb == 256) && cost < best_cost) { best_cost = cost; bestNb = nb; bestVc = Vc; }
-        if (nb >= Np) break;
+
+    // Row block of a tiles, vocabulary chunk of b tiles.
+    auto bytes_needed = [&](int64_t a, int64_t b) {
+        return (double)fixed + (double)round_up(a * 256 * D * 4, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
+    };
+    BackwardModel model{cus, D, gemm_tile_for(D)};
+    int best_a = 1, best_b = 1;
+    if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
+        best_a = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
+        best_b = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
+    } else {
+        double best_cost = 1e300;
+        const int a_max = p->TT < 64 ? p->TT : 64, b_max = p->VT < 128 ? p->VT : 128;
+        for (int a = 1; a <= a_max; ++a) {
+            for (int b = 1; b <= b_max; ++b) {
+                if (bytes_needed(a, b) > (double)budget && !(a == 1 && b == 1)) break;
+                const int nblk = (p->TT + a - 1) / a, a_last = p->TT - (nblk - 1) * a;
+                const int nch = (p->VT + b - 1) / b, b_last = p->VT - (nch - 1) * b;
+                // the first row block overwrites dW, later ones add to it
+                auto block_cost = [&](int aa, bool beta) {
+                    return (nch - 1) * model.step(aa, b, beta) + model.step(aa, b_last, beta);
+                };
+                const double cost = (nblk == 1) ? block_cost(a_last, false)
+                                                : block_cost(a, false) + (nblk - 2) * block_cost(a, true) + block_cost(a_last, true);
+                if (cost < best_cost) { best_cost = cost; best_a = a; best_b = b; }
+            }
+        }
     }
-    p->Nb = bestNb;
-    p->Vc = bestVc;
+    p->Nb = (int64_t)best_a * 256;
+    p->Vc = (int64_t)best_b * 256;
     p->off_status = 0;
     p->off_partials = 256;
     p->off_dhacc = p->off_partials + partial_bytes;
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 4, 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
+    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, *p, true};
     return true;
 }
 
@@ -651,52 +746,85 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
     if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return CCE_ERR_HIP;
     if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return CCE_ERR_HIP;
 
-    // 256-wide hidden tiles when D divides evenly, else 128-wide ones (D = 896 = 7 x 128)
-    const bool big = (D % 256 == 0);
-    const int bn = big ? TileBig::BN : TileNarrow::BN;
-    const int d_tiles = (int)((D + bn - 1) / bn);
+    const GemmTile gt = gemm_tile_for(D);
+    const int d_tiles = (int)((D + gt.bn - 1) / gt.bn);
+    const int per256 = 256 / gt.bm;                               // contraction row tiles per 256 rows
+
+    // The [row block x vocabulary chunk] steps in execution order.
+    struct Step { int64_t r0, rows, v0, cols; int row_tiles, v_tiles; bool first_chunk, last_chunk; };
+    std::vector<Step> steps;
+    const int64_t nchunks = (V + p.Vc - 1) / p.Vc;
     for (int64_t r0 = 0; r0 < N; r0 += p.Nb) {
-        const int64_t rows = (N - r0 < p.Nb) ? (N - r0) : p.Nb;            // valid rows in this block
-        const int row_tiles = (int)((rows + 255) / 256);
-        const int64_t nchunks = (V + p.Vc - 1) / p.Vc;
+        const int64_t rows = (N - r0 < p.Nb) ? (N - r0) : p.Nb;
         for (int64_t c = 0; c < nchunks; ++c) {
             const int64_t v0 = c * p.Vc;
-            const int64_t cols = (V - v0 < p.Vc) ? (V - v0) : p.Vc;       // valid vocabulary columns
-            const int v_tiles = (int)((cols + 255) / 256);
-            const int ldg = v_tiles * 256;                                  // chunk is stored densely padded
-            // 1. gradient tiles of this [row block x chunk]
-            {
-                ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
-                hipLaunchKernelGGL(grad_tile_kernel, dim3(row_tiles * v_tiles), dim3(kThreads), grad_lds, stream,
-                                   hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
-                                   (int)r0, row_tiles, (int)v0, v_tiles, G, ldg);
-            }
-            const bool last = (c == nchunks - 1);
-            // 2a. dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
-            GemmJob dh;
-            dh.A = G; dh.lda = ldg; dh.a_free_n = row_tiles * 256; dh.a_k_n = ldg;
-            dh.B = (const void*)((const uint16_t*)weight + (size_t)v0 * D); dh.ldb = (int)D; dh.b_k_n = (int)cols;
-            dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = row_tiles * d_tiles;
-            dh.m_valid = (int)rows; dh.n_valid = (int)D;
-            dh.out_f32 = dhacc; dh.ld_out = D; dh.beta = c > 0 ? 1 : 0;
-            dh.out_bf16 = last ? (uint16_t*)dHidden + (size_t)r0 * D : (uint16_t*)nullptr; dh.ld_out_bf16 = D;
-            // 2b. dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
-            GemmJob dw;
-            dw.A = G; dw.lda = ldg; dw.a_free_n = ldg; dw.a_k_n = row_tiles * 256;
-            dw.B = (const void*)((const uint16_t*)hidden + (size_t)r0 * D); dw.ldb = (int)D; dw.b_k_n = (int)rows;
-            dw.k_total = row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = v_tiles * d_tiles;
-            dw.m_valid = (int)cols; dw.n_valid = (int)D;
-            dw.out_f32 = dW + (size_t)v0 * D; dw.ld_out = D; dw.beta = (r0 > 0 || accumulate_dW) ? 1 : 0;
-            dw.out_bf16 = nullptr; dw.ld_out_bf16 = 0;
-            const int work = dh.n_work + dw.n_work;
+            const int64_t cols = (V - v0 < p.Vc) ? (V - v0) : p.Vc;
+            steps.push_back({r0, rows, v0, cols, (int)((rows + 255) / 256), (int)((cols + 255) / 256), c == 0, c == nchunks - 1});
+        }
+    }
+    const int K = (int)steps.size();
+
+    for (int k = 0; k < K; ++k) {
+        const Step& st = steps[k];
+        const int ldg = st.v_tiles * 256;                       // the chunk is stored densely padded
+        // 1. gradient tiles of this [row block x chunk]
+        {
+            ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
+            hipLaunchKernelGGL(grad_tile_kernel, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
+                               hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
+                               (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg);
+        }
+        // 2. both contractions in one launch
+        // dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
+        GemmJob dh;
+        dh.a_kmajor = 1;
+        dh.A = G; dh.lda = ldg; dh.a_free_n = st.row_tiles * 256; dh.a_k_n = ldg;
+        dh.B = (const void*)((const uint16_t*)weight + (size_t)st.v0 * D); dh.ldb = (int)D; dh.b_k_n = (int)st.cols;
+        dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = st.row_tiles * per256 * d_tiles;
+        dh.m_valid = (int)st.rows; dh.n_valid = (int)D;
+        dh.out_f32 = dhacc; dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
+        dh.out_bf16 = st.last_chunk ? (uint16_t*)dHidden + (size_t)st.r0 * D : (uint16_t*)nullptr; dh.ld_out_bf16 = D;
+        // dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
+        GemmJob dw;
+        dw.a_kmajor = 0;
+        dw.A = G; dw.lda = ldg; dw.a_free_n = ldg; dw.a_k_n = st.row_tiles * 256;
+        dw.B = (const void*)((const uint16_t*)hidden + (size_t)st.r0 * D); dw.ldb = (int)D; dw.b_k_n = (int)st.rows;
+        dw.k_total = st.row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = st.v_tiles * per256 * d_tiles;
+        dw.m_valid = (int)st.cols; dw.n_valid = (int)D;
+        dw.out_f32 = dW + (size_t)st.v0 * D; dw.ld_out = D; dw.beta = (st.r0 > 0 || accumulate_dW) ? 1 : 0;
+        dw.out_bf16 = nullptr; dw.ld_out_bf16 = 0;
+        const bool dh_first = dh.k_total >= dw.k_total;          // longer reduction first
+        const GemmJob& first = dh_first ? dh : dw;
+        const GemmJob& second = dh_first ? dw : dh;
+        const int work = dh.n_work + dw.n_work;
+
+        {
             ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
-            if (big)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, dh, dw);
+            if (gt.kind == 0)
+                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
             else
-                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, dh, dw);
+                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
         }
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_set_backward_tiling(int row_tiles, int vocab_tiles) {
+    if (row_tiles < 0 || vocab_tiles < 0 || (row_tiles == 0) != (vocab_tiles == 0)) return CCE_ERR_INVALID;
+    g_force_row_tiles = row_tiles;
+    g_force_vocab_tiles = vocab_tiles;
+    return CCE_OK;
+}
+
+int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int* vocab_tiles) {
+    Plan p;
+    if (!row_tiles || !vocab_tiles) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || V <= 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (!make_plan(N, D, V, &p)) return CCE_ERR_INVALID;
+    *row_tiles = (int)(p.Nb / 256);
+    *vocab_tiles = (int)(p.Vc / 256);
     return CCE_OK;
 }
 

@@ -72,12 +72,33 @@ def test_config_tiny_per_row_dloss_with_nan_at_ignored(B):
     (700, 128, 3000),     # 3 ragged token tiles, 12 vocabulary tiles with a tail
     (300, 64, 257),       # one vocabulary row past a tile boundary
     (513, 192, 1100),     # D = 3 K-slices
-    (1000, 896, 4500),    # the benchmark's hidden size
+    (1000, 896, 4500),    # the benchmark's hidden size (128 x 224 contraction tiles)
+    (333, 448, 1300),     # two 224-wide hidden tiles, ragged everywhere
+    (600, 512, 2100),     # 256 x 256 contraction tiles
 ])
 def test_ragged_shapes(B, shape):
     N, D, V = shape
     w = I.make_workload(I.custom_spec(N, D, V, seed=11, ignore_frac=0.2))
     check_against_oracle(B, w, w.dloss_var, f"ragged{shape}")
+
+
+@pytest.mark.parametrize("tiling", [(1, 1), (2, 3), (3, 2), (1, 64)])
+def test_backward_is_invariant_to_the_chunking(B, tiling):
+    """Row-block and vocabulary-chunk sizes are free parameters of the chunk-level backward
+    algorithm: every tiling must meet the oracle, and agree with the automatic one up to
+    fp32 summation order."""
+    w = I.make_workload(I.custom_spec(700, 896, 3000, seed=12, ignore_frac=0.2))
+    try:
+        B.set_backward_tiling(0, 0)
+        base = run_both(B, w, w.dloss_var)
+        B.set_backward_tiling(*tiling)
+        assert B.get_backward_tiling(700, 896, 3000) == (min(tiling[0], 3), min(tiling[1], 12))
+        check_against_oracle(B, w, w.dloss_var, f"tiling{tiling}")
+        got = run_both(B, w, w.dloss_var)
+    finally:
+        B.set_backward_tiling(0, 0)
+    assert np.array_equal(base[0], got[0]) and np.array_equal(base[1], got[1])     # forward untouched
+    assert rel_fro(got[2], base[2]) <= 5e-3 and rel_fro(got[3], base[3]) <= 1e-5
 
 
 def test_single_token_single_class(B):
