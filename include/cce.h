@@ -35,7 +35,7 @@
  *     aborts across this boundary.  On an error return nothing was enqueued.
  *   - `workspace` is caller-owned device scratch of at least
  *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
- *     O(N*D + tile): per-row partial (max, sum-exp) pairs, an fp32 dHidden
+ *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, an fp32 dHidden
  *     accumulator for one row block and one bf16 [row block x vocab chunk]
  *     gradient chunk; it never scales with N*V.  Contents are scratch: nothing
  *     needs to survive between forward and backward except what the caller
@@ -114,6 +114,38 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
                  int64_t N, int64_t D, int64_t V, int32_t ignore_index,
                  void* dHidden, float* dW, int accumulate_dW,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Loss variants in the same kernels (epilogue-only changes): label smoothing and z-loss of the
+ * paper's mathematical-foundations section, and the mean reduction of its cross-entropy
+ * kernel.  With eps = label_smoothing in [0, 1) and lambda = z_loss >= 0, for non-ignored rows
+ *   loss_i = (1 - eps) (lse_i - z_iy) + eps (lse_i - mean_v z_iv) + lambda lse_i^2
+ *            (smoothed cross-entropy definition; z-loss definition)
+ *   dloss_i/dz_iv = (1 + 2 lambda lse_i) softmax_iv - (1 - eps) [v == y_i] - eps / V
+ *            (cross-entropy gradient proposition; z-loss gradient proposition)
+ * lse is the plain log-sum-exp in every variant.  eps = lambda = 0 is cce_forward / cce_backward.
+ *
+ * cce_forward_ex: as cce_forward, plus
+ *   mean_loss  out fp32 [1]  device, may be NULL: sum_i loss_i / n_valid over the rows whose label
+ *              is neither ignore_index nor out of range (0 when there are none)
+ * cce_backward_ex: as cce_backward, plus
+ *   dloss      may be NULL = mean reduction: every row's upstream gradient is
+ *              grad_scale / n_valid (grad_scale = gradient of the scalar mean loss, normally 1),
+ *              n_valid counted on the device; when dloss is given grad_scale is not used
+ * Both return CCE_ERR_INVALID for eps outside [0, 1) or a negative / non-finite lambda.
+ */
+int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                   int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                   float label_smoothing, float z_loss,
+                   float* loss, float* lse, float* mean_loss,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+int cce_backward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                    const float* lse, const float* dloss, float grad_scale,
+                    int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                    float label_smoothing, float z_loss,
+                    void* dHidden, float* dW, int accumulate_dW,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Tuning aid: forces the backward tiling to row blocks of `row_tiles` x 256 tokens and

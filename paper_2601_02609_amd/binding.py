@@ -23,6 +23,7 @@ CCE_STATUS_BAD_LABEL = 1
 EXPORTED_SYMBOLS = [
     "cce_version", "cce_strerror", "cce_last_hip_error", "cce_workspace_bytes",
     "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
+    "cce_forward_ex", "cce_backward_ex",
     "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
     "cce_get_backward_tiling",
 ]
@@ -65,6 +66,11 @@ def lib() -> ctypes.CDLL:
     L.cce_forward.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
     L.cce_backward.restype = ctypes.c_int
     L.cce_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, ctypes.c_int, vp, sz, vp]
+    f32 = ctypes.c_float
+    L.cce_forward_ex.restype = ctypes.c_int
+    L.cce_forward_ex.argtypes = [vp, vp, vp, i64, i64, i64, i32, f32, f32, vp, vp, vp, vp, sz, vp]
+    L.cce_backward_ex.restype = ctypes.c_int
+    L.cce_backward_ex.argtypes = [vp, vp, vp, vp, vp, f32, i64, i64, i64, i32, f32, f32, vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_read_status.restype = ctypes.c_int
     L.cce_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     L.cce_profile_begin.restype = ctypes.c_int
@@ -165,6 +171,71 @@ def cce_backward(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tenso
                             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     if rc != CCE_OK:
         raise CCEError(rc, "cce_backward")
+    return d_hidden, d_weight
+
+
+def cce_forward_ex(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,
+                   ignore_index: int = -100, *, label_smoothing: float = 0.0, z_loss: float = 0.0,
+                   want_mean: bool = False, workspace: Optional[torch.Tensor] = None,
+                   loss: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None):
+    """Loss variants of the forward: (loss [N], lse [N], mean_loss [1] or None)."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden.device)
+    if loss is None:
+        loss = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    mean = torch.empty(1, dtype=torch.float32, device=hidden.device) if want_mean else None
+    rc = lib().cce_forward_ex(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), N, D, V,
+                              ignore_index, label_smoothing, z_loss, loss.data_ptr(), lse.data_ptr(),
+                              mean.data_ptr() if mean is not None else None,
+                              workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_forward_ex")
+    return loss, lse, mean
+
+
+def cce_backward_ex(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,
+                    lse: torch.Tensor, dloss: Optional[torch.Tensor], ignore_index: int = -100, *,
+                    grad_scale: float = 1.0, label_smoothing: float = 0.0, z_loss: float = 0.0,
+                    workspace: Optional[torch.Tensor] = None,
+                    d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                    accumulate_dw: bool = False,
+                    stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Loss variants of the backward; dloss=None selects mean reduction (grad_scale / n_valid)."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    if dloss is not None:
+        _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(V, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (V, D), "d_weight")
+    rc = lib().cce_backward_ex(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(),
+                               lse.data_ptr(), dloss.data_ptr() if dloss is not None else None, grad_scale,
+                               N, D, V, ignore_index, label_smoothing, z_loss,
+                               d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_backward_ex")
     return d_hidden, d_weight
 
 

@@ -77,9 +77,13 @@ __device__ __forceinline__ void md_merge(float& m, float& d, float m2, float d2)
 // block: the running max / sum of a token is lane-local until the very end.
 // partials[token * S + split] = (m, d) with m in the log2 domain (m = max_v z * log2 e).
 // ------------------------------------------------------------------------------------------
+// SUMZ (label smoothing only): the sum of a token's logits over the vocabulary split is carried
+// along as well, partial_sumz[token * S + split]; the smoothed loss needs their mean.
+template <bool SUMZ>
 __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
         const void* __restrict__ H, const void* __restrict__ W,
-        int N, int D, int V, int TT, int VT, int S, float2* __restrict__ partials) {
+        int N, int D, int V, int TT, int VT, int S, float2* __restrict__ partials,
+        float* __restrict__ partial_sumz) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -97,9 +101,9 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     OperandTile<true, Cfg::BN> Bop;
     Bop.init(H, D, tt * Cfg::BN, N, D);
 
-    float run_m[Cfg::TN], run_d[Cfg::TN];
+    float run_m[Cfg::TN], run_d[Cfg::TN], run_z[Cfg::TN];
 #pragma unroll
-    for (int bn = 0; bn < Cfg::TN; ++bn) { run_m[bn] = -INFINITY; run_d[bn] = 0.f; }
+    for (int bn = 0; bn < Cfg::TN; ++bn) { run_m[bn] = -INFINITY; run_d[bn] = 0.f; run_z[bn] = 0.f; }
 
     for (int vt = vt0; vt < vt1; ++vt) {
         f32x16 acc[Cfg::TM][Cfg::TN];
@@ -141,6 +145,14 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
                 for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[bm][bn][r], kLog2e, -ms));
             run_d[bn] = run_d[bn] * fast_exp2(run_m[bn] - ms) + sum;
             run_m[bn] = mn;
+            if (SUMZ) {
+                float sz = 0.f;
+#pragma unroll
+                for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sz += (acc[bm][bn][r] == -INFINITY) ? 0.f : acc[bm][bn][r];   // masked tail rows
+                run_z[bn] += sz;
+            }
         }
     }
 
@@ -149,24 +161,32 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const float om = __shfl_xor(run_m[bn], 32), od = __shfl_xor(run_d[bn], 32);
         md_merge(run_m[bn], run_d[bn], om, od);
+        if (SUMZ) run_z[bn] += __shfl_xor(run_z[bn], 32);
     }
     // the WM waves stacked along the vocabulary dimension share token columns: merge via LDS
     CCE_LDS f32x2* red = (CCE_LDS f32x2*)smem;        // [WM][BN]
+    CCE_LDS float* redz = (CCE_LDS float*)(smem + Cfg::WM * Cfg::BN * 8);   // [WM][BN]
     if (l < 32) {
 #pragma unroll
-        for (int bn = 0; bn < Cfg::TN; ++bn)
+        for (int bn = 0; bn < Cfg::TN; ++bn) {
             red[wm * Cfg::BN + acc_col<Cfg>(bn)] = f32x2{run_m[bn], run_d[bn]};
+            if (SUMZ) redz[wm * Cfg::BN + acc_col<Cfg>(bn)] = run_z[bn];
+        }
     }
     __syncthreads();
     if (threadIdx.x < Cfg::BN) {
         const int tok = tt * Cfg::BN + threadIdx.x;
-        float m = -INFINITY, d = 0.f;
+        float m = -INFINITY, d = 0.f, z = 0.f;
 #pragma unroll
         for (int w = 0; w < Cfg::WM; ++w) {
             const f32x2 p = red[w * Cfg::BN + threadIdx.x];
             md_merge(m, d, p.x, p.y);
+            if (SUMZ) z += redz[w * Cfg::BN + threadIdx.x];
         }
-        if (tok < N) partials[(size_t)tok * S + s] = make_float2(m, d);
+        if (tok < N) {
+            partials[(size_t)tok * S + s] = make_float2(m, d);
+            if (SUMZ) partial_sumz[(size_t)tok * S + s] = z;
+        }
     }
 }
 
@@ -175,7 +195,8 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void finalize_kernel(
         const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, const int32_t* __restrict__ labels,
-        const float2* __restrict__ partials, int N, int D, int V, int S, int32_t ignore_index,
+        const float2* __restrict__ partials, const float* __restrict__ partial_sumz,
+        int N, int D, int V, int S, int32_t ignore_index, float label_smoothing, float z_loss,
         float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status) {
     const int l = threadIdx.x & 63;
     const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -190,15 +211,17 @@ __global__ __launch_bounds__(256) void finalize_kernel(
         }
         return;
     }
-    float m = -INFINITY, d = 0.f;
+    float m = -INFINITY, d = 0.f, sumz = 0.f;
     for (int i = l; i < S; i += 64) {
         const float2 p = partials[(size_t)tok * S + i];
         md_merge(m, d, p.x, p.y);
+        if (partial_sumz) sumz += partial_sumz[(size_t)tok * S + i];
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
         const float om = __shfl_xor(m, o), od = __shfl_xor(d, o);
         md_merge(m, d, om, od);
+        sumz += __shfl_xor(sumz, o);
     }
     // label logit: fp32 dot product of the two bf16 rows
     const uint16_t* h = H + (size_t)tok * D;
@@ -214,16 +237,73 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     if (l == 0) {
         const float out = (m + fast_log2(d)) * kLn2;
         lse[tok] = out;
-        loss[tok] = out - zy;
+        // (1 - eps) (lse - z_y) + eps (lse - mean_v z_v) + lambda lse^2   (smoothed cross-entropy
+        // and z-loss definitions); eps = lambda = 0 leaves lse - z_y
+        float t = out - zy;
+        if (label_smoothing != 0.f) t = (1.f - label_smoothing) * t + label_smoothing * (out - sumz / (float)V);
+        if (z_loss != 0.f) t = fmaf(z_loss * out, out, t);
+        loss[tok] = t;
     }
 }
 
 __global__ void clear_status_kernel(int32_t* status) { if (threadIdx.x == 0) status[0] = 0; }
 
+// Number of rows that take part in the loss (label in range and not ignore_index), counted by
+// one workgroup.  Integer counting: the result does not depend on the order.
+__device__ __forceinline__ int count_valid_rows(const int32_t* labels, int N, int V, int32_t ignore_index, int* scratch) {
+    int c = 0;
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+        const int32_t y = labels[i];
+        c += (y != ignore_index && y >= 0 && y < V) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = c;
+    __syncthreads();
+    int total = 0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) total += scratch[w];
+    __syncthreads();
+    return total;
+}
+
+// Mean reduction of the backward: every row's upstream gradient is grad_scale / n_valid
+// (the materialising cross-entropy kernel of the paper divides the gradient by the number
+// of non-ignored rows).  One workgroup of 1024 threads; out is a single float.
+__global__ __launch_bounds__(1024) void mean_scale_kernel(const int32_t* __restrict__ labels, int N, int V,
+                                                          int32_t ignore_index, float grad_scale, float* __restrict__ out) {
+    __shared__ int scratch[16];
+    const int n = count_valid_rows(labels, N, V, ignore_index, scratch);
+    if (threadIdx.x == 0) out[0] = n > 0 ? grad_scale / (float)n : 0.f;
+}
+
+// Mean of the per-token losses over the non-ignored rows (0 when there are none).  One
+// workgroup; each thread sums a strided subset in fp32, then a fixed tree: the result is
+// reproducible run to run.
+__global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict__ loss, const int32_t* __restrict__ labels,
+                                                         int N, int V, int32_t ignore_index, float* __restrict__ out) {
+    __shared__ int scratch[16];
+    __shared__ float fsum[16];
+    const int n = count_valid_rows(labels, N, V, ignore_index, scratch);
+    float a = 0.f;
+    for (int i = threadIdx.x; i < N; i += blockDim.x) a += loss[i];     // ignored rows hold 0
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) a += __shfl_xor(a, o);
+    if ((threadIdx.x & 63) == 0) fsum[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < 16; ++w) t += fsum[w];
+        out[0] = n > 0 ? t / (float)n : 0.f;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Backward, step 1: recompute one logit tile and store the bf16 gradient tile
-//   G[i, v] = dloss_i * (exp(z_iv - lse_i) - [v == y_i]),   0 where the row is ignored /
-//   beyond N or the column is beyond V.
+//   G[i, v] = dloss_i * ((1 + 2 lambda lse_i) exp(z_iv - lse_i) - (1 - eps) [v == y_i] - eps / V),
+//   0 where the row is ignored / beyond N or the column is beyond V.  eps = lambda = 0 is the
+//   plain softmax - onehot of the CCE backward theorem; eps is the label-smoothing weight
+//   (smoothed cross-entropy definition), lambda the z-loss weight (z-loss gradient
+//   proposition).  dloss == nullptr selects mean reduction: dloss_i = *mean_scale for all i.
 // Same orientation as the forward (lane owns a token column).  The tile is staged in LDS as
 // [token][vocab] and written to the scratch chunk G (row-major [rows_pad][ldg], vocab
 // contiguous) with full 512-byte rows.
@@ -231,8 +311,8 @@ __global__ void clear_status_kernel(int32_t* status) { if (threadIdx.x == 0) sta
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
         const void* __restrict__ H, const void* __restrict__ W, const int32_t* __restrict__ labels,
-        const float* __restrict__ lse, const float* __restrict__ dloss,
-        int N, int D, int V, int32_t ignore_index,
+        const float* __restrict__ lse, const float* __restrict__ dloss, const float* __restrict__ mean_scale,
+        int N, int D, int V, int32_t ignore_index, float label_smoothing, float z_loss,
         int row0, int n_row_tiles, int v0, int n_v_tiles,
         uint16_t* __restrict__ G, int ldg) {
     typedef TileBig Cfg;
@@ -258,14 +338,20 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     // per-token scalars of this lane's columns, and the liveness of the row this thread will
     // flag, are fetched before the main loop so that their latency hides under it
     int32_t col_y[Cfg::TN];
-    float col_dl[Cfg::TN], col_nl2[Cfg::TN];
+    float col_sp[Cfg::TN], col_ch[Cfg::TN], col_ncs[Cfg::TN], col_nl2[Cfg::TN];
+    const float uniform_dl = dloss ? 0.f : mean_scale[0];
+    const float eps_over_v = label_smoothing / (float)V;
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int tok = tok0 + acc_col<Cfg>(bn);
         const bool tok_ok = tok < N;
         col_y[bn] = tok_ok ? labels[tok] : -1;
-        col_dl[bn] = tok_ok ? dloss[tok] : 0.f;
-        col_nl2[bn] = tok_ok ? -lse[tok] * kLog2e : 0.f;
+        const float dl = tok_ok ? (dloss ? dloss[tok] : uniform_dl) : 0.f;
+        const float ls = tok_ok ? lse[tok] : 0.f;
+        col_sp[bn] = dl * fmaf(2.f * z_loss, ls, 1.f);      // factor of the softmax term
+        col_ch[bn] = dl * (1.f - label_smoothing);          // subtracted at the label
+        col_ncs[bn] = -dl * eps_over_v;                     // added everywhere
+        col_nl2[bn] = -ls * kLog2e;
     }
     bool row_live = false;
     if (threadIdx.x < Cfg::BN && tok0 + (int)threadIdx.x < N) {
@@ -287,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int col = acc_col<Cfg>(bn);
         const int32_t y = col_y[bn];
-        const float dl = col_dl[bn];
+        const float sp = col_sp[bn], ch = col_ch[bn], ncs = col_ncs[bn];
         const float nl2 = col_nl2[bn];
         const int yrel = y - (vt0 + wm * (Cfg::TM * 32));     // label relative to this wave's rows
         const bool hit = (yrel >= 0) && (yrel < Cfg::TM * 32);
@@ -297,17 +383,17 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
             for (int r4 = 0; r4 < 4; ++r4) {
                 float g[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) g[e] = fast_exp2(fmaf(acc[bm][bn][r4 * 4 + e], kLog2e, nl2));
+                for (int e = 0; e < 4; ++e) g[e] = fmaf(fast_exp2(fmaf(acc[bm][bn][r4 * 4 + e], kLog2e, nl2)), sp, ncs);
                 const int rrel = bm * 32 + 8 * r4 + 4 * (l >> 5);      // first of 4 consecutive rows
                 if (hit) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) g[e] -= (rrel + e == yrel) ? 1.f : 0.f;
+                    for (int e = 0; e < 4; ++e) g[e] -= (rrel + e == yrel) ? ch : 0.f;
                 }
                 const int vrow = wm * (Cfg::TM * 32) + rrel;            // row inside the tile
                 const int vglob = vt0 + vrow;
                 union { __bf16 h[4]; u32x2 u; } pk;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)((vglob + e < V) ? g[e] * dl : 0.f);
+                for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)((vglob + e < V) ? g[e] : 0.f);
                 *(CCE_LDS u32x2*)(smem + col * kGRowBytes + vrow * 2) = pk.u;
             }
         }
@@ -518,7 +604,7 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 struct Plan {
     int TT, VT, S;              // forward: token tiles, vocabulary tiles, vocabulary splits
     int64_t Nb, Vc;             // backward: rows per row block, vocabulary columns per chunk (multiples of 256)
-    size_t off_status, off_partials, off_dhacc, off_g, total;
+    size_t off_status, off_partials, off_sumz, off_dhacc, off_g, total;
 };
 
 // Workspace budget: 1 % of the materialised fp32 logits, but never below a floor that
@@ -605,7 +691,9 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     if (S < 1) S = 1;
     p->S = S;
 
-    const size_t partial_bytes = (size_t)round_up((int64_t)N * S * 8, 256);
+    // per (token, split): (max, sum-exp) pair + the logit sum that label smoothing needs
+    const size_t md_bytes = (size_t)round_up((int64_t)N * S * 8, 256);
+    const size_t partial_bytes = md_bytes + (size_t)round_up((int64_t)N * S * 4, 256);
     size_t budget = (size_t)((double)N * (double)V * 4.0 * 0.01);
     if (budget < kBudgetFloor) budget = kBudgetFloor;
     const size_t fixed = 256 + partial_bytes;
@@ -641,6 +729,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->Vc = (int64_t)best_b * 256;
     p->off_status = 0;
     p->off_partials = 256;
+    p->off_sumz = p->off_partials + md_bytes;
     p->off_dhacc = p->off_partials + partial_bytes;
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 4, 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
@@ -699,47 +788,78 @@ size_t cce_materialised_logit_bytes(int64_t N, int64_t V) {
     return (size_t)N * (size_t)V * 4u;
 }
 
-int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
-                int64_t N, int64_t D, int64_t V, int32_t ignore_index,
-                float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+static bool variant_ok(float label_smoothing, float z_loss) {
+    return label_smoothing >= 0.f && label_smoothing < 1.f && z_loss >= 0.f && isfinite(z_loss);
+}
+
+int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                   int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                   float label_smoothing, float z_loss,
+                   float* loss, float* lse, float* mean_loss,
+                   void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
     if (!loss || !lse) return CCE_ERR_INVALID;
-    if (((uintptr_t)loss | (uintptr_t)lse) & 3) return CCE_ERR_INVALID;
+    if (((uintptr_t)loss | (uintptr_t)lse | (uintptr_t)mean_loss) & 3) return CCE_ERR_INVALID;
+    if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
     if (rc != CCE_OK) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
     int32_t* status = (int32_t*)(ws + p.off_status);
     float2* partials = (float2*)(ws + p.off_partials);
+    const bool smooth = label_smoothing != 0.f;
+    float* sumz = smooth ? (float*)(ws + p.off_sumz) : (float*)nullptr;
 
-    if (!allow_big_lds(lse_partial_kernel, TileBig::kLdsBytes)) return CCE_ERR_HIP;
+    if (!allow_big_lds(lse_partial_kernel<false>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
+    if (!allow_big_lds(lse_partial_kernel<true>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     {
         ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
-        hipLaunchKernelGGL(lse_partial_kernel, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                           hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials);
+        if (smooth)
+            hipLaunchKernelGGL(lse_partial_kernel<true>, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz);
+        else
+            hipLaunchKernelGGL(lse_partial_kernel<false>, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz);
     }
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
-                       (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials,
-                       (int)N, (int)D, (int)V, p.S, ignore_index, loss, lse, status);
+                       (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials, (const float*)sumz,
+                       (int)N, (int)D, (int)V, p.S, ignore_index, label_smoothing, z_loss, loss, lse, status);
+    if (mean_loss)
+        hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
+                           (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
 
-int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
-                 const float* lse, const float* dloss,
-                 int64_t N, int64_t D, int64_t V, int32_t ignore_index,
-                 void* dHidden, float* dW, int accumulate_dW,
-                 void* workspace, size_t workspace_bytes, void* stream_) {
+int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
+                int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+    return cce_forward_ex(hidden, weight, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+                          workspace, workspace_bytes, stream_);
+}
+
+int cce_backward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                    const float* lse, const float* dloss, float grad_scale,
+                    int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                    float label_smoothing, float z_loss,
+                    void* dHidden, float* dW, int accumulate_dW,
+                    void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
-    if (!lse || !dloss || !dHidden || !dW) return CCE_ERR_INVALID;
+    if (!lse || !dHidden || !dW) return CCE_ERR_INVALID;
     if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
+    if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
     if (rc != CCE_OK) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
     float* dhacc = (float*)(ws + p.off_dhacc);
     uint16_t* G = (uint16_t*)(ws + p.off_g);
+    // mean reduction: the common upstream gradient grad_scale / n_valid lives in the status block
+    float* mean_scale = (float*)(ws + p.off_status + 64);
+    if (!dloss)
+        hipLaunchKernelGGL(mean_scale_kernel, dim3(1), dim3(1024), 0, stream,
+                           labels, (int)N, (int)V, ignore_index, grad_scale, mean_scale);
 
     const int grad_lds = (256 * kGRowBytes + 256 > TileBig::kLdsBytes) ? 256 * kGRowBytes + 256 : TileBig::kLdsBytes;
     if (!allow_big_lds(grad_tile_kernel, grad_lds)) return CCE_ERR_HIP;
@@ -771,7 +891,8 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
         {
             ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
             hipLaunchKernelGGL(grad_tile_kernel, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
-                               hidden, weight, labels, lse, dloss, (int)N, (int)D, (int)V, ignore_index,
+                               hidden, weight, labels, lse, dloss, (const float*)mean_scale,
+                               (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
                                (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg);
         }
         // 2. both contractions in one launch
@@ -808,6 +929,16 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
+}
+
+int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
+                 const float* lse, const float* dloss,
+                 int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                 void* dHidden, float* dW, int accumulate_dW,
+                 void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!dloss) return CCE_ERR_INVALID;
+    return cce_backward_ex(hidden, weight, labels, lse, dloss, 1.f, N, D, V, ignore_index, 0.f, 0.f,
+                           dHidden, dW, accumulate_dW, workspace, workspace_bytes, stream_);
 }
 
 int cce_set_backward_tiling(int row_tiles, int vocab_tiles) {
