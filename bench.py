@@ -176,6 +176,7 @@ def main() -> int:
         "pct_bf16_mfma_peak": round(100 * executed_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
         "workspace_bytes": int(ws.numel()),
         "workspace_pct_of_logits": round(100.0 * ws.numel() / B.materialised_logit_bytes(N, V), 3),
+        "backward_tiling_256": list(B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
         "roofline": roofline, "cpu_baseline": cpu,
     }

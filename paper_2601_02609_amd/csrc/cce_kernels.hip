@@ -427,7 +427,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 // LDS of grad_gemm_kernel: the main loop's stages or the epilogue staging, whichever is larger.
 constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
     const int one_pass = bm * (bn + 8) * 4;
-    const int staging = one_pass <= 150 * 1024 ? one_pass : one_pass / 2;
+    const int staging = one_pass <= 150 * 1024 ? one_pass : 64 * (bn + 8) * 4;
     return staging > main_loop ? staging : main_loop;
 }
 constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, TileBig::BN);
@@ -463,14 +463,38 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     // Epilogue through LDS so that global memory sees 16-byte accesses along full rows:
     // the fp32 tile is staged [rows][BN + 8 floats] (the padding keeps the two 128-byte
     // row segments a wavefront writes per instruction in different halves of the banks),
-    // half of the rows at a time when the whole tile does not fit.
-    constexpr int kPasses = (Cfg::BM * (Cfg::BN + 8) * 4 <= 150 * 1024) ? 1 : 2;
+    // 64 rows at a time when the whole tile does not fit (which also keeps the number of
+    // chunks a thread holds per pass, and with it the register pressure, small).
+    constexpr int kPasses = (Cfg::BM * (Cfg::BN + 8) * 4 <= 150 * 1024) ? 1 : Cfg::BM / 64;
     constexpr int kRowsPerPass = Cfg::BM / kPasses;
     constexpr int kRowBytes = (Cfg::BN + 8) * 4;
     constexpr int kChunksPerRow = Cfg::BN / 4;                 // 16-byte chunks
+    constexpr int kRowsPerIter = kThreads / kChunksPerRow;
+    constexpr int kIters = kRowsPerPass / kRowsPerIter;        // chunks per thread and pass
+    static_assert(kThreads % kChunksPerRow == 0 && kRowsPerPass % kRowsPerIter == 0, "whole rows per iteration");
     static_assert(kRowsPerPass * kRowBytes <= 160 * 1024, "epilogue staging must fit the LDS");
-    const int wave_row0 = wave_m<Cfg>() * (Cfg::TM * 32);
     static_assert(Cfg::KG == 1 || kPasses == 1, "K-group reduction shares the one-pass staging");
+    const int wave_row0 = wave_m<Cfg>() * (Cfg::TM * 32);
+    // this thread's chunks of a pass: rows it * kRowsPerIter + threadIdx.x / kChunksPerRow
+    const int my_chunk = threadIdx.x % kChunksPerRow, my_row = threadIdx.x / kChunksPerRow;
+    const int col = ni * Cfg::BN + my_chunk * 4;
+    const bool col_ok = col < j.n_valid;                       // n_valid is a multiple of 8: whole chunks
+
+    // When the tile is added to what the output already holds, those values are fetched
+    // as early as possible -- all chunks of a pass at once, right after the main loop /
+    // the previous pass -- so that their latency hides under the staging through LDS
+    // (whose barriers wait for LDS traffic only).
+    f32x4 old[kIters];
+    auto fetch_old = [&](int pr0) {
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int row = mi * Cfg::BM + pr0 + it * kRowsPerIter + my_row;
+            old[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (j.beta && col_ok && row < j.m_valid) old[it] = *(const f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col);
+        }
+    };
+    fetch_old(0);
+
     if (Cfg::KG == 2) {
         // the two K groups hold partial sums of the same positions: group 1 parks its
         // accumulators in the staging area, group 0 adds them to its own
@@ -483,7 +507,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
                     for (int r = 0; r < 16; ++r)
                         *(CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
         }
-        __syncthreads();
+        barrier_lds_only();
         if (wave_kg<Cfg>() == 0) {
 #pragma unroll
             for (int bm = 0; bm < Cfg::TM; ++bm)
@@ -498,36 +522,40 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) {
         const int pr0 = pass * kRowsPerPass;
-        if (wave_kg<Cfg>() == 0 && wave_row0 >= pr0 && wave_row0 < pr0 + kRowsPerPass) {
+        if (wave_kg<Cfg>() == 0) {
 #pragma unroll
-            for (int bm = 0; bm < Cfg::TM; ++bm)
+            for (int bm = 0; bm < Cfg::TM; ++bm) {
+                const int brow = wave_row0 + bm * 32;           // the 32-row block lies in one pass
+                if (brow < pr0 || brow >= pr0 + kRowsPerPass) continue;
 #pragma unroll
                 for (int bn = 0; bn < Cfg::TN; ++bn)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         *(CCE_LDS float*)(smem + (acc_row<Cfg>(bm, r) - pr0) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
+            }
         }
-        __syncthreads();
-        // thread -> (row, 16-byte chunk) pairs of the staged rows, consecutive threads along a row
-#pragma unroll 4
-        for (int idx = threadIdx.x; idx < kRowsPerPass * kChunksPerRow; idx += kThreads) {
-            const int lrow = idx / kChunksPerRow, chunk = idx % kChunksPerRow;
-            const int col = ni * Cfg::BN + chunk * 4;
-            const int row = mi * Cfg::BM + pr0 + lrow;
-            if (col >= j.n_valid || row >= j.m_valid) continue;      // n_valid is a multiple of 8: whole chunks
-            f32x4 v = *(const CCE_LDS f32x4*)(smem + lrow * kRowBytes + chunk * 16);
-            float* p = j.out_f32 + (size_t)row * j.ld_out + col;
-            if (j.beta) v += *(const f32x4*)p;
+        barrier_lds_only();
+        f32x4 v[kIters];
+#pragma unroll
+        for (int it = 0; it < kIters; ++it)
+            v[it] = *(const CCE_LDS f32x4*)(smem + (it * kRowsPerIter + my_row) * kRowBytes + my_chunk * 16) + old[it];
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int row = mi * Cfg::BM + pr0 + it * kRowsPerIter + my_row;
+            if (!col_ok || row >= j.m_valid) continue;
             if (j.out_bf16) {
                 union { __bf16 h[4]; u32x2 u; } cv;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[e];
+                for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[it][e];
                 *(u32x2*)(j.out_bf16 + (size_t)row * j.ld_out_bf16 + col) = cv.u;
             } else {
-                *(f32x4*)p = v;
+                *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
             }
         }
-        if (pass + 1 < kPasses) __syncthreads();
+        if (pass + 1 < kPasses) {
+            fetch_old(pr0 + kRowsPerPass);
+            barrier_lds_only();                               // staging is free for the next pass
+        }
     }
 }
 

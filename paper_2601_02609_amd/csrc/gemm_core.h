@@ -219,6 +219,12 @@ __device__ __forceinline__ void barrier_pending_loads() {
     else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(PENDING) : "memory");
 }
 
+// Workgroup barrier for data exchanged through LDS only: waits for this thread's LDS
+// traffic, not for its outstanding global loads (which __syncthreads would also drain).
+__device__ __forceinline__ void barrier_lds_only() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // acc[bm][bn] += A-tile * B-tile^T over K slices [0, ceil(k_total / 64)).  The operands
 // clamp / meet zero padding so that reads past k_total contribute zero.
 // `smem` must hold Cfg::kLdsBytes.  Ends with a workgroup barrier, after which the LDS may
