@@ -1,0 +1,61 @@
+"""fp64 CPU oracle for RMSNorm, the step in front of the LM head.
+
+TEST INFRASTRUCTURE ONLY: the slow, plain definition the HIP kernels are checked against.
+It shares no code with the GPU path, imports nothing from the package and is never called
+from the product path.
+
+What it computes, and where the paper defines it:
+
+* forward   y_i = x_i / r * gamma_i,  r = sqrt(mean_j x_j^2 + eps)   (RMSNorm definition in the
+            mathematical-foundations section; the fused forward kernel also stores
+            rstd = 1 / r per row for the backward)
+* backward  the derivative of that definition for an upstream gradient g = dL/dy:
+              dx_i = rstd * (gamma_i g_i - xhat_i * c),   xhat = x * rstd,
+              c    = mean_j (g_j gamma_j xhat_j)
+              dgamma_i = sum over rows of g_i xhat_i
+            Reading taken: the paper's backward proposition and its kernel listing both
+            print the second term of dx with a stray factor gamma_i (and the proposition
+            drops the 1/d of the mean); neither is the derivative of the printed forward
+            unless gamma = 1.  The oracle is the derivative itself, which the pins
+            (torch autograd, central finite differences) confirm; dgamma is as printed.
+
+Inputs are bf16 bit patterns (uint16), widened exactly to float64; everything after that is
+float64.  Pinned by tests/test_next_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = ["widen_bf16", "forward", "backward"]
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    bits = np.asarray(bits)
+    if bits.dtype != np.uint16:
+        raise TypeError("bf16 tensors are passed as uint16 bit patterns")
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def forward(x_bits: np.ndarray, gamma_bits: np.ndarray, eps: float):
+    """(y [N, D], rstd [N]) in float64."""
+    x = widen_bf16(x_bits)
+    gamma = widen_bf16(gamma_bits)
+    if x.ndim != 2 or gamma.shape != (x.shape[1],):
+        raise ValueError("x is [N, D], gamma is [D]")
+    rstd = 1.0 / np.sqrt((x * x).mean(axis=1) + eps)
+    return x * rstd[:, None] * gamma[None, :], rstd
+
+
+def backward(x_bits: np.ndarray, gamma_bits: np.ndarray, dy_bits: np.ndarray, eps: float):
+    """(dx [N, D], dgamma [D]) in float64 for the upstream gradient dy (bf16 bits)."""
+    x = widen_bf16(x_bits)
+    gamma = widen_bf16(gamma_bits)
+    g = widen_bf16(dy_bits)
+    if g.shape != x.shape:
+        raise ValueError("dy has the shape of x")
+    rstd = 1.0 / np.sqrt((x * x).mean(axis=1) + eps)
+    xhat = x * rstd[:, None]
+    c = (g * gamma[None, :] * xhat).mean(axis=1)
+    dx = rstd[:, None] * (gamma[None, :] * g - xhat * c[:, None])
+    dgamma = (g * xhat).sum(axis=0)
+    return dx, dgamma
