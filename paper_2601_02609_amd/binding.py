@@ -26,6 +26,9 @@ EXPORTED_SYMBOLS = [
     "cce_forward_ex", "cce_backward_ex",
     "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
     "cce_get_backward_tiling",
+    # include/cce_aux.h
+    "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
+    "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
 ]
 KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
@@ -81,6 +84,20 @@ def lib() -> ctypes.CDLL:
     L.cce_set_backward_tiling.argtypes = [ctypes.c_int, ctypes.c_int]
     L.cce_get_backward_tiling.restype = ctypes.c_int
     L.cce_get_backward_tiling.argtypes = [i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
+    L.cce_rmsnorm_workspace_bytes.restype = sz
+    L.cce_rmsnorm_workspace_bytes.argtypes = [i64, i64]
+    L.cce_rmsnorm_forward.restype = ctypes.c_int
+    L.cce_rmsnorm_forward.argtypes = [vp, vp, i64, i64, f32, vp, vp, vp]
+    L.cce_rmsnorm_backward.restype = ctypes.c_int
+    L.cce_rmsnorm_backward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_sumsq_workspace_bytes.restype = sz
+    L.cce_sumsq_workspace_bytes.argtypes = []
+    L.cce_grad_sumsq.restype = ctypes.c_int
+    L.cce_grad_sumsq.argtypes = [vp, i64, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_clip_coef.restype = ctypes.c_int
+    L.cce_clip_coef.argtypes = [vp, f32, f32, vp, vp]
+    L.cce_adamw_step.restype = ctypes.c_int
+    L.cce_adamw_step.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i64, vp, vp]
     _lib = L
     return L
 
@@ -278,3 +295,93 @@ def profile_end() -> dict:
     if rc != CCE_OK:
         raise CCEError(rc, "cce_profile_end")
     return {KERNEL_FAMILIES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+# ---------------------------------------------------------------- include/cce_aux.h
+
+def _rc(rc: int, where: str) -> None:
+    if rc != CCE_OK:
+        raise CCEError(rc, where)
+
+
+def cce_rmsnorm_forward(x: torch.Tensor, gamma: torch.Tensor, eps: float, *,
+                        stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(y bf16 [N, D], rstd fp32 [N]) of bf16 x [N, D] and gamma [D]."""
+    N, D = x.shape
+    _check(x, torch.bfloat16, (N, D), "x")
+    _check(gamma, torch.bfloat16, (D,), "gamma")
+    y = torch.empty_like(x)
+    rstd = torch.empty(N, dtype=torch.float32, device=x.device)
+    _rc(lib().cce_rmsnorm_forward(x.data_ptr(), gamma.data_ptr(), N, D, eps, y.data_ptr(), rstd.data_ptr(),
+                                  _stream_ptr(stream)), "cce_rmsnorm_forward")
+    return y, rstd
+
+
+def cce_rmsnorm_backward(x: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor, *,
+                         dgamma: Optional[torch.Tensor] = None, accumulate_dgamma: bool = False,
+                         stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(dx bf16 [N, D], dgamma fp32 [D]) for the upstream gradient dy bf16 [N, D]."""
+    N, D = x.shape
+    _check(x, torch.bfloat16, (N, D), "x")
+    _check(gamma, torch.bfloat16, (D,), "gamma")
+    _check(rstd, torch.float32, (N,), "rstd")
+    _check(dy, torch.bfloat16, (N, D), "dy")
+    n = int(lib().cce_rmsnorm_workspace_bytes(N, D))
+    if n == 0:
+        raise CCEError(CCE_ERR_UNSUPPORTED, "cce_rmsnorm_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=x.device)
+    dx = torch.empty_like(x)
+    if dgamma is None:
+        if accumulate_dgamma:
+            raise ValueError("accumulate_dgamma needs an existing dgamma")
+        dgamma = torch.empty(D, dtype=torch.float32, device=x.device)
+    _check(dgamma, torch.float32, (D,), "dgamma")
+    _rc(lib().cce_rmsnorm_backward(x.data_ptr(), gamma.data_ptr(), rstd.data_ptr(), dy.data_ptr(), N, D,
+                                   dx.data_ptr(), dgamma.data_ptr(), 1 if accumulate_dgamma else 0,
+                                   ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "cce_rmsnorm_backward")
+    return dx, dgamma
+
+
+def cce_grad_sumsq(grad: torch.Tensor, sumsq: Optional[torch.Tensor] = None, accumulate: bool = False, *,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Device fp64 [1] holding sum g^2 (added to `sumsq` when accumulate)."""
+    if grad.dtype != torch.float32 or not grad.is_contiguous() or not grad.is_cuda:
+        raise ValueError("grad: expected a contiguous cuda float32 tensor")
+    if sumsq is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing sumsq")
+        sumsq = torch.empty(1, dtype=torch.float64, device=grad.device)
+    _check(sumsq, torch.float64, (1,), "sumsq")
+    ws = torch.empty(int(lib().cce_sumsq_workspace_bytes()), dtype=torch.uint8, device=grad.device)
+    _rc(lib().cce_grad_sumsq(grad.data_ptr(), grad.numel(), sumsq.data_ptr(), 1 if accumulate else 0,
+                             ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "cce_grad_sumsq")
+    return sumsq
+
+
+def cce_clip_coef(sumsq: torch.Tensor, max_norm: float, eps_norm: float = 1e-6, *,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Device fp32 [1]: min(1, max_norm / (sqrt(sumsq) + eps_norm))."""
+    _check(sumsq, torch.float64, (1,), "sumsq")
+    coef = torch.empty(1, dtype=torch.float32, device=sumsq.device)
+    _rc(lib().cce_clip_coef(sumsq.data_ptr(), max_norm, eps_norm, coef.data_ptr(), _stream_ptr(stream)),
+        "cce_clip_coef")
+    return coef
+
+
+def cce_adamw_step(param: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, step: int, *,
+                   lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                   weight_decay: float = 0.0, param_bf16: Optional[torch.Tensor] = None,
+                   clip_coef: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    """In-place fused AdamW step on fp32 param / m / v; optionally also writes the bf16 copy."""
+    n = param.numel()
+    for name, t in (("param", param), ("grad", grad), ("m", m), ("v", v)):
+        if t.dtype != torch.float32 or t.numel() != n or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError(f"{name}: expected a contiguous cuda float32 tensor of {n} elements")
+    if param_bf16 is not None and (param_bf16.dtype != torch.bfloat16 or param_bf16.numel() != n
+                                   or not param_bf16.is_contiguous()):
+        raise ValueError("param_bf16: expected a contiguous bfloat16 tensor of the same size")
+    _rc(lib().cce_adamw_step(param.data_ptr(), param_bf16.data_ptr() if param_bf16 is not None else None,
+                             grad.data_ptr(), m.data_ptr(), v.data_ptr(), n, lr, beta1, beta2, eps, weight_decay,
+                             step, clip_coef.data_ptr() if clip_coef is not None else None,
+                             _stream_ptr(stream)), "cce_adamw_step")

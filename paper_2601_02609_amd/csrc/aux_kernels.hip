@@ -1,0 +1,367 @@
+// libcce, auxiliary kernels: the final RMSNorm in front of the LM head and the fused AdamW
+// step (with the clipping coefficient) behind it.  C ABI declared in include/cce_aux.h.
+// All of them stream their tensors once: the bound is HBM bandwidth, so the work is 16-byte
+// coalesced accesses, wavefront shuffles for the row reductions and no atomics (two-stage
+// fixed-order sums keep the results reproducible).
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/cce.h"
+#include "../../include/cce_aux.h"
+#include "host_util.h"
+
+namespace cce {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int au32x4;
+typedef __attribute__((ext_vector_type(4))) float af32x4;
+
+constexpr int kNormMaxChunks = 16;      // 16-byte chunks per lane and row: D <= 16 * 64 * 8 = 8192
+constexpr int kNormBackwardBlocks = 512;
+constexpr int kSumsqBlocks = 1024;
+
+__device__ __forceinline__ void unpack8(const au32x4& p, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(p[i] << 16);
+        f[2 * i + 1] = __uint_as_float(p[i] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ au32x4 pack8(const float (&f)[8]) {
+    au32x4 p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        union { __bf16 h[2]; unsigned int u; } cv;
+        cv.h[0] = (__bf16)f[2 * i];
+        cv.h[1] = (__bf16)f[2 * i + 1];
+        p[i] = cv.u;
+    }
+    return p;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm forward (RMSNorm definition; fused forward kernel: one pass, rstd cached).
+// One wavefront per row; lane l holds the 16-byte chunks l, l + 64, ... of the row in
+// registers between the reduction and the scaling, so x is read once.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
+        const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, int N, int D, float eps,
+        uint16_t* __restrict__ y, float* __restrict__ rstd_out) {
+    const int l = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const int chunks = D >> 3;
+    const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
+    au32x4 xv[kNormMaxChunks];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormMaxChunks; ++i) {
+        const int c = l + 64 * i;
+        if (c < chunks) {
+            xv[i] = xr[c];
+            float f[8];
+            unpack8(xv[i], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
+        }
+    }
+    ss = wave_sum(ss);
+    const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
+    if (l == 0) rstd_out[row] = rstd;
+    const au32x4* gr = (const au32x4*)gamma;
+    au32x4* yr = (au32x4*)(y + (size_t)row * D);
+#pragma unroll
+    for (int i = 0; i < kNormMaxChunks; ++i) {
+        const int c = l + 64 * i;
+        if (c < chunks) {
+            float f[8], g[8];
+            unpack8(xv[i], f);
+            unpack8(gr[c], g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * g[e];
+            yr[c] = pack8(f);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm backward.  Wavefronts walk the rows with a grid stride; per row
+//   c = mean_j(dy_j gamma_j xhat_j),  dx_j = rstd (gamma_j dy_j - xhat_j c),  xhat = x rstd,
+// and each lane adds dy_j xhat_j of its columns to a private dgamma partial.  The four
+// wavefronts of a workgroup then add their partials through LDS and the workgroup writes one
+// partial row; dgamma_reduce_kernel sums those rows in a fixed order.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
+        const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, const float* __restrict__ rstd_in,
+        const uint16_t* __restrict__ dy, int N, int D, uint16_t* __restrict__ dx, float* __restrict__ partials) {
+    __shared__ float red[4][64 * 8];
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int chunks = D >> 3;
+    const au32x4* gr = (const au32x4*)gamma;
+    float dg[kNormMaxChunks][8];
+#pragma unroll
+    for (int i = 0; i < kNormMaxChunks; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dg[i][e] = 0.f;
+
+    for (int row = blockIdx.x * 4 + w; row < N; row += gridDim.x * 4) {
+        const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
+        const au32x4* dyr = (const au32x4*)(dy + (size_t)row * D);
+        au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
+        const float rstd = rstd_in[row];
+        au32x4 xv[kNormMaxChunks], gv[kNormMaxChunks];
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < kNormMaxChunks; ++i) {
+            const int c = l + 64 * i;
+            if (c < chunks) {
+                xv[i] = xr[c];
+                gv[i] = dyr[c];
+                float xf[8], gf[8], ga[8];
+                unpack8(xv[i], xf);
+                unpack8(gv[i], gf);
+                unpack8(gr[c], ga);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float xh = xf[e] * rstd;
+                    t = fmaf(gf[e] * ga[e], xh, t);
+                    dg[i][e] = fmaf(gf[e], xh, dg[i][e]);
+                }
+            }
+        }
+        const float cmean = wave_sum(t) / (float)D;
+#pragma unroll
+        for (int i = 0; i < kNormMaxChunks; ++i) {
+            const int c = l + 64 * i;
+            if (c < chunks) {
+                float xf[8], gf[8], ga[8], o[8];
+                unpack8(xv[i], xf);
+                unpack8(gv[i], gf);
+                unpack8(gr[c], ga);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = rstd * (ga[e] * gf[e] - xf[e] * rstd * cmean);
+                dxr[c] = pack8(o);
+            }
+        }
+    }
+    // add the four wavefronts' partials, 512 columns (one chunk index i) at a time
+#pragma unroll
+    for (int i = 0; i < kNormMaxChunks; ++i) {
+        if (64 * i < chunks) {                       // uniform over the workgroup
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[w][l * 8 + e] = dg[i][e];
+            __syncthreads();
+#pragma unroll
+            for (int j = threadIdx.x; j < 512; j += 256) {
+                const int col = 512 * i + j;
+                if (col < D) partials[(size_t)blockIdx.x * D + col] = red[0][j] + red[1][j] + red[2][j] + red[3][j];
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restrict__ partials, int blocks, int D,
+                                                            float* __restrict__ dgamma, int accumulate) {
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= D) return;
+    float s = 0.f;
+    for (int b = 0; b < blocks; ++b) s += partials[(size_t)b * D + col];
+    dgamma[col] = accumulate ? dgamma[col] + s : s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Global-norm clipping coefficient, resident on the GPU (gradient-clipping strategies).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sumsq_partial_kernel(const float* __restrict__ g, int64_t n, double* __restrict__ partials) {
+    __shared__ double red[4];
+    const int64_t n4 = n >> 2;
+    const af32x4* g4 = (const af32x4*)g;
+    float s = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const af32x4 v = g4[i];
+        s = fmaf(v[0], v[0], s); s = fmaf(v[1], v[1], s); s = fmaf(v[2], v[2], s); s = fmaf(v[3], v[3], s);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) { const float t = g[(n4 << 2) + threadIdx.x]; s = fmaf(t, t, s); }
+    double d = (double)s;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = d;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(64) void sumsq_final_kernel(const double* __restrict__ partials, int blocks,
+                                                         double* __restrict__ sumsq, int accumulate) {
+    double d = 0.0;
+    for (int i = threadIdx.x; i < blocks; i += 64) d += partials[i];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o);
+    if (threadIdx.x == 0) sumsq[0] = accumulate ? sumsq[0] + d : d;
+}
+
+__global__ void clip_coef_kernel(const double* __restrict__ sumsq, float max_norm, float eps_norm, float* __restrict__ coef) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const double c = (double)max_norm / (sqrt(sumsq[0]) + (double)eps_norm);
+        coef[0] = c < 1.0 ? (float)c : 1.0f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused AdamW (fused AdamW kernel: every tensor is loaded once and stored once).
+// ------------------------------------------------------------------------------------------
+struct AdamwArgs {
+    float lr, beta1, beta2, eps, decay_factor, inv_bc1, inv_bc2;
+};
+
+__device__ __forceinline__ void adamw_one(float& p, float g, float& m, float& v, const AdamwArgs& a) {
+    p *= a.decay_factor;                                   // decoupled weight decay, before the update
+    m = a.beta1 * m + (1.f - a.beta1) * g;
+    v = a.beta2 * v + (1.f - a.beta2) * g * g;
+    const float m_hat = m * a.inv_bc1, v_hat = v * a.inv_bc2;
+    p -= a.lr * (m_hat / (sqrtf(v_hat) + a.eps));
+}
+
+__global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ param, uint16_t* __restrict__ param_bf16,
+                                                    const float* __restrict__ grad, float* __restrict__ m,
+                                                    float* __restrict__ v, int64_t n, AdamwArgs a,
+                                                    const float* __restrict__ clip_coef) {
+    const float clip = clip_coef ? clip_coef[0] : 1.f;
+    const int64_t n4 = n >> 2;
+    af32x4* p4 = (af32x4*)param;
+    const af32x4* g4 = (const af32x4*)grad;
+    af32x4* m4 = (af32x4*)m;
+    af32x4* v4 = (af32x4*)v;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        af32x4 p = p4[i], g = g4[i], mm = m4[i], vv = v4[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float pe = p[e], me = mm[e], ve = vv[e];
+            adamw_one(pe, g[e] * clip, me, ve, a);
+            p[e] = pe; mm[e] = me; vv[e] = ve;
+        }
+        p4[i] = p; m4[i] = mm; v4[i] = vv;
+        if (param_bf16) {
+            union { __bf16 h[4]; unsigned long long u; } cv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)p[e];
+            *(unsigned long long*)(param_bf16 + (i << 2)) = cv.u;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const int64_t i = (n4 << 2) + threadIdx.x;
+        float p = param[i], mm = m[i], vv = v[i];
+        adamw_one(p, grad[i] * clip, mm, vv, a);
+        param[i] = p; m[i] = mm; v[i] = vv;
+        if (param_bf16) { union { __bf16 h; uint16_t u; } cv; cv.h = (__bf16)p; param_bf16[i] = cv.u; }
+    }
+}
+
+static bool norm_shape_ok(int64_t N, int64_t D) {
+    return N > 0 && D > 0 && D % 64 == 0 && D <= (int64_t)kNormMaxChunks * 512 && N <= ((int64_t)1 << 30);
+}
+
+static int norm_backward_blocks(int64_t N) {
+    const int64_t want = (N + 3) / 4;
+    return (int)(want < kNormBackwardBlocks ? want : kNormBackwardBlocks);
+}
+
+}  // namespace cce
+
+using namespace cce;
+
+extern "C" {
+
+size_t cce_rmsnorm_workspace_bytes(int64_t N, int64_t D) {
+    if (!norm_shape_ok(N, D)) return 0;
+    return (size_t)round_up((int64_t)norm_backward_blocks(N) * D * 4, 256);
+}
+
+int cce_rmsnorm_forward(const void* x, const void* gamma, int64_t N, int64_t D, float eps,
+                        void* y, float* rstd, void* stream_) {
+    if (!x || !gamma || !y || !rstd) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || !(eps >= 0.f)) return CCE_ERR_INVALID;
+    if (!norm_shape_ok(N, D)) return CCE_ERR_UNSUPPORTED;
+    if (((uintptr_t)x | (uintptr_t)gamma | (uintptr_t)y) & 15) return CCE_ERR_INVALID;
+    if ((uintptr_t)rstd & 3) return CCE_ERR_INVALID;
+    hipLaunchKernelGGL(rmsnorm_forward_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, (hipStream_t)stream_,
+                       (const uint16_t*)x, (const uint16_t*)gamma, (int)N, (int)D, eps, (uint16_t*)y, rstd);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dy,
+                         int64_t N, int64_t D, void* dx, float* dgamma, int accumulate_dgamma,
+                         void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!x || !gamma || !rstd || !dy || !dx || !dgamma || !workspace) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0) return CCE_ERR_INVALID;
+    if (!norm_shape_ok(N, D)) return CCE_ERR_UNSUPPORTED;
+    if (((uintptr_t)x | (uintptr_t)gamma | (uintptr_t)dy | (uintptr_t)dx) & 15) return CCE_ERR_INVALID;
+    if (((uintptr_t)rstd | (uintptr_t)dgamma) & 3) return CCE_ERR_INVALID;
+    if (((uintptr_t)workspace & 255) || workspace_bytes < cce_rmsnorm_workspace_bytes(N, D)) return CCE_ERR_INVALID;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int blocks = norm_backward_blocks(N);
+    float* partials = (float*)workspace;
+    hipLaunchKernelGGL(rmsnorm_backward_kernel, dim3(blocks), dim3(256), 0, stream,
+                       (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D,
+                       (uint16_t*)dx, partials);
+    hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, stream,
+                       (const float*)partials, blocks, (int)D, dgamma, accumulate_dgamma ? 1 : 0);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+size_t cce_sumsq_workspace_bytes(void) { return (size_t)kSumsqBlocks * sizeof(double); }
+
+int cce_grad_sumsq(const float* grad, int64_t n, double* sumsq, int accumulate,
+                   void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!grad || !sumsq || !workspace || n <= 0) return CCE_ERR_INVALID;
+    if (((uintptr_t)grad & 15) || ((uintptr_t)sumsq & 7) || ((uintptr_t)workspace & 255)) return CCE_ERR_INVALID;
+    if (workspace_bytes < cce_sumsq_workspace_bytes()) return CCE_ERR_INVALID;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t want = ((n >> 2) + 255) / 256;
+    const int blocks = (int)(want < 1 ? 1 : (want < kSumsqBlocks ? want : kSumsqBlocks));
+    hipLaunchKernelGGL(sumsq_partial_kernel, dim3(blocks), dim3(256), 0, stream, grad, n, (double*)workspace);
+    hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(64), 0, stream, (const double*)workspace, blocks, sumsq,
+                       accumulate ? 1 : 0);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_clip_coef(const double* sumsq, float max_norm, float eps_norm, float* clip_coef, void* stream_) {
+    if (!sumsq || !clip_coef || !(max_norm > 0.f) || !(eps_norm >= 0.f)) return CCE_ERR_INVALID;
+    hipLaunchKernelGGL(clip_coef_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream_, sumsq, max_norm, eps_norm, clip_coef);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_adamw_step(float* param, void* param_bf16, const float* grad, float* m, float* v, int64_t n,
+                   float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                   const float* clip_coef, void* stream_) {
+    if (!param || !grad || !m || !v || n <= 0 || step < 1) return CCE_ERR_INVALID;
+    if (((uintptr_t)param | (uintptr_t)grad | (uintptr_t)m | (uintptr_t)v) & 15) return CCE_ERR_INVALID;
+    if ((uintptr_t)param_bf16 & 7) return CCE_ERR_INVALID;
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps >= 0.f && lr >= 0.f && weight_decay >= 0.f))
+        return CCE_ERR_INVALID;
+    AdamwArgs a;
+    a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
+    a.decay_factor = 1.f - lr * weight_decay;
+    a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+    a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    const int64_t want = ((n >> 2) + 255) / 256;
+    const int blocks = (int)(want < 1 ? 1 : (want < 8192 ? want : 8192));
+    hipLaunchKernelGGL(adamw_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream_,
+                       param, (uint16_t*)param_bf16, grad, m, v, n, a, clip_coef);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+}  // extern "C"

@@ -21,6 +21,7 @@
 
 #include "../../include/cce.h"
 #include "gemm_core.h"
+#include "host_util.h"
 
 namespace cce {
 
@@ -574,12 +575,7 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
-static thread_local int g_last_hip_error = 0;
-
-static inline bool hip_ok(hipError_t e) {
-    if (e != hipSuccess) { g_last_hip_error = (int)e; return false; }
-    return true;
-}
+thread_local int g_last_hip_error = 0;
 
 // Optional per-kernel-family timing with HIP events (cce_profile_begin / cce_profile_end).
 // Off by default; when on, every launch of a timed family is bracketed by two events on the
@@ -627,7 +623,6 @@ static int device_cu_count() {
     return n;
 }
 
-static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 struct Plan {
     int TT, VT, S;              // forward: token tiles, vocabulary tiles, vocabulary splits

@@ -1,4 +1,4 @@
-"""The C-ABI shared library loads and exports every symbol include/cce.h declares (no GPU needed),
+"""The C-ABI shared library loads and exports every symbol include/*.h declares (no GPU needed),
 and its host-only entry points behave as documented."""
 import os
 import re
@@ -18,9 +18,15 @@ def L():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "cce.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_and_binding_agree():
@@ -39,6 +45,10 @@ def test_host_only_entry_points(L):
     # the paper's memory equation: 8 x 1024 tokens x 151,936 x 4 bytes = 4.97 GB
     assert binding.materialised_logit_bytes(8192, 151936) == 8192 * 151936 * 4
     assert binding.materialised_logit_bytes(0, 5) == 0
+    # auxiliary entry points: workspace sizes are pure host functions
+    assert L.cce_rmsnorm_workspace_bytes(8192, 896) > 0 and L.cce_rmsnorm_workspace_bytes(8192, 100) == 0
+    assert L.cce_rmsnorm_workspace_bytes(8192, 16384) == 0          # beyond the row a wavefront holds
+    assert L.cce_sumsq_workspace_bytes() >= 8
 
 
 def test_workspace_is_small_and_independent_of_NV(L):
