@@ -305,20 +305,26 @@ def _rc(rc: int, where: str) -> None:
 
 
 def cce_rmsnorm_forward(x: torch.Tensor, gamma: torch.Tensor, eps: float, *,
+                        y: Optional[torch.Tensor] = None, rstd: Optional[torch.Tensor] = None,
                         stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """(y bf16 [N, D], rstd fp32 [N]) of bf16 x [N, D] and gamma [D]."""
     N, D = x.shape
     _check(x, torch.bfloat16, (N, D), "x")
     _check(gamma, torch.bfloat16, (D,), "gamma")
-    y = torch.empty_like(x)
-    rstd = torch.empty(N, dtype=torch.float32, device=x.device)
+    if y is None:
+        y = torch.empty_like(x)
+    if rstd is None:
+        rstd = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(y, torch.bfloat16, (N, D), "y")
+    _check(rstd, torch.float32, (N,), "rstd")
     _rc(lib().cce_rmsnorm_forward(x.data_ptr(), gamma.data_ptr(), N, D, eps, y.data_ptr(), rstd.data_ptr(),
                                   _stream_ptr(stream)), "cce_rmsnorm_forward")
     return y, rstd
 
 
 def cce_rmsnorm_backward(x: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor, *,
-                         dgamma: Optional[torch.Tensor] = None, accumulate_dgamma: bool = False,
+                         dx: Optional[torch.Tensor] = None, dgamma: Optional[torch.Tensor] = None,
+                         accumulate_dgamma: bool = False, workspace: Optional[torch.Tensor] = None,
                          stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """(dx bf16 [N, D], dgamma fp32 [D]) for the upstream gradient dy bf16 [N, D]."""
     N, D = x.shape
@@ -329,8 +335,10 @@ def cce_rmsnorm_backward(x: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tenso
     n = int(lib().cce_rmsnorm_workspace_bytes(N, D))
     if n == 0:
         raise CCEError(CCE_ERR_UNSUPPORTED, "cce_rmsnorm_workspace_bytes")
-    ws = torch.empty(n, dtype=torch.uint8, device=x.device)
-    dx = torch.empty_like(x)
+    ws = workspace if workspace is not None else torch.empty(n, dtype=torch.uint8, device=x.device)
+    if dx is None:
+        dx = torch.empty_like(x)
+    _check(dx, torch.bfloat16, (N, D), "dx")
     if dgamma is None:
         if accumulate_dgamma:
             raise ValueError("accumulate_dgamma needs an existing dgamma")
@@ -343,6 +351,7 @@ def cce_rmsnorm_backward(x: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tenso
 
 
 def cce_grad_sumsq(grad: torch.Tensor, sumsq: Optional[torch.Tensor] = None, accumulate: bool = False, *,
+                   workspace: Optional[torch.Tensor] = None,
                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """Device fp64 [1] holding sum g^2 (added to `sumsq` when accumulate)."""
     if grad.dtype != torch.float32 or not grad.is_contiguous() or not grad.is_cuda:
@@ -352,7 +361,8 @@ def cce_grad_sumsq(grad: torch.Tensor, sumsq: Optional[torch.Tensor] = None, acc
             raise ValueError("accumulate needs an existing sumsq")
         sumsq = torch.empty(1, dtype=torch.float64, device=grad.device)
     _check(sumsq, torch.float64, (1,), "sumsq")
-    ws = torch.empty(int(lib().cce_sumsq_workspace_bytes()), dtype=torch.uint8, device=grad.device)
+    ws = workspace if workspace is not None else torch.empty(int(lib().cce_sumsq_workspace_bytes()),
+                                                             dtype=torch.uint8, device=grad.device)
     _rc(lib().cce_grad_sumsq(grad.data_ptr(), grad.numel(), sumsq.data_ptr(), 1 if accumulate else 0,
                              ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "cce_grad_sumsq")
     return sumsq

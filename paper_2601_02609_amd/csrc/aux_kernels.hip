@@ -52,6 +52,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 // One wavefront per row; lane l holds the 16-byte chunks l, l + 64, ... of the row in
 // registers between the reduction and the scaling, so x is read once.
 // ------------------------------------------------------------------------------------------
+template <int CH>      // 16-byte chunks a lane holds per row: D <= CH * 512
 __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
         const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, int N, int D, float eps,
         uint16_t* __restrict__ y, float* __restrict__ rstd_out) {
@@ -60,10 +61,10 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
     if (row >= N) return;
     const int chunks = D >> 3;
     const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
-    au32x4 xv[kNormMaxChunks];
+    au32x4 xv[CH];
     float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < kNormMaxChunks; ++i) {
+    for (int i = 0; i < CH; ++i) {
         const int c = l + 64 * i;
         if (c < chunks) {
             xv[i] = xr[c];
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
     const au32x4* gr = (const au32x4*)gamma;
     au32x4* yr = (au32x4*)(y + (size_t)row * D);
 #pragma unroll
-    for (int i = 0; i < kNormMaxChunks; ++i) {
+    for (int i = 0; i < CH; ++i) {
         const int c = l + 64 * i;
         if (c < chunks) {
             float f[8], g[8];
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
 // wavefronts of a workgroup then add their partials through LDS and the workgroup writes one
 // partial row; dgamma_reduce_kernel sums those rows in a fixed order.
 // ------------------------------------------------------------------------------------------
+template <int CH>
 __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
         const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, const float* __restrict__ rstd_in,
         const uint16_t* __restrict__ dy, int N, int D, uint16_t* __restrict__ dx, float* __restrict__ partials) {
@@ -106,25 +108,31 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int chunks = D >> 3;
     const au32x4* gr = (const au32x4*)gamma;
-    float dg[kNormMaxChunks][8];
+    float dg[CH][8];
 #pragma unroll
-    for (int i = 0; i < kNormMaxChunks; ++i)
+    for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e) dg[i][e] = 0.f;
 
-    for (int row = blockIdx.x * 4 + w; row < N; row += gridDim.x * 4) {
+    // A row's x and dy are loaded one row ahead of their use (two register sets, A and B),
+    // so that every wavefront always has a row of loads in flight.
+    auto load_row = [&](au32x4 (&xv)[CH], au32x4 (&gv)[CH], int row) {
         const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
         const au32x4* dyr = (const au32x4*)(dy + (size_t)row * D);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = l + 64 * i;
+            if (c < chunks) { xv[i] = xr[c]; gv[i] = dyr[c]; }
+        }
+    };
+    auto process_row = [&](const au32x4 (&xv)[CH], const au32x4 (&gv)[CH], int row) {
         au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
         const float rstd = rstd_in[row];
-        au32x4 xv[kNormMaxChunks], gv[kNormMaxChunks];
         float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < kNormMaxChunks; ++i) {
+        for (int i = 0; i < CH; ++i) {
             const int c = l + 64 * i;
             if (c < chunks) {
-                xv[i] = xr[c];
-                gv[i] = dyr[c];
                 float xf[8], gf[8], ga[8];
                 unpack8(xv[i], xf);
                 unpack8(gv[i], gf);
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
         }
         const float cmean = wave_sum(t) / (float)D;
 #pragma unroll
-        for (int i = 0; i < kNormMaxChunks; ++i) {
+        for (int i = 0; i < CH; ++i) {
             const int c = l + 64 * i;
             if (c < chunks) {
                 float xf[8], gf[8], ga[8], o[8];
@@ -151,10 +159,62 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
                 dxr[c] = pack8(o);
             }
         }
+    };
+    const int stride = gridDim.x * 4;
+    int row = blockIdx.x * 4 + w;
+    if constexpr (CH <= 8) {
+        au32x4 xa[CH], ga_[CH], xb[CH], gb[CH];
+        if (row < N) load_row(xa, ga_, row);
+        while (row < N) {
+            const int r2 = row + stride;
+            if (r2 < N) load_row(xb, gb, r2);
+            process_row(xa, ga_, row);
+            if (r2 >= N) break;
+            const int r3 = r2 + stride;
+            if (r3 < N) load_row(xa, ga_, r3);
+            process_row(xb, gb, r2);
+            row = r3;
+        }
+    } else {
+        // The widest rows (D > 4096) leave no registers to hold a row next to the dgamma
+        // partials: x and dy are read a second time (from L2) for dx.
+        for (; row < N; row += stride) {
+            const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
+            const au32x4* dyr = (const au32x4*)(dy + (size_t)row * D);
+            au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
+            const float rstd = rstd_in[row];
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int c = l + 64 * i;
+                if (c < chunks) {
+                    float xf[8], gf[8], ga[8];
+                    unpack8(xr[c], xf);
+                    unpack8(dyr[c], gf);
+                    unpack8(gr[c], ga);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float xh = xf[e] * rstd;
+                        t = fmaf(gf[e] * ga[e], xh, t);
+                        dg[i][e] = fmaf(gf[e], xh, dg[i][e]);
+                    }
+                }
+            }
+            const float cmean = wave_sum(t) / (float)D;
+            for (int c = l; c < chunks; c += 64) {
+                float xf[8], gf[8], ga[8], o[8];
+                unpack8(xr[c], xf);
+                unpack8(dyr[c], gf);
+                unpack8(gr[c], ga);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = rstd * (ga[e] * gf[e] - xf[e] * rstd * cmean);
+                dxr[c] = pack8(o);
+            }
+        }
     }
     // add the four wavefronts' partials, 512 columns (one chunk index i) at a time
 #pragma unroll
-    for (int i = 0; i < kNormMaxChunks; ++i) {
+    for (int i = 0; i < CH; ++i) {
         if (64 * i < chunks) {                       // uniform over the workgroup
 #pragma unroll
             for (int e = 0; e < 8; ++e) red[w][l * 8 + e] = dg[i][e];
@@ -169,13 +229,30 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
     }
 }
 
+// dgamma[col] = sum over the workgroups' partial rows, in a fixed order: a workgroup owns 64
+// columns; its four wavefronts each add every fourth row, then the four sums are added.
 __global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restrict__ partials, int blocks, int D,
                                                             float* __restrict__ dgamma, int accumulate) {
-    const int col = blockIdx.x * 256 + threadIdx.x;
-    if (col >= D) return;
-    float s = 0.f;
-    for (int b = 0; b < blocks; ++b) s += partials[(size_t)b * D + col];
-    dgamma[col] = accumulate ? dgamma[col] + s : s;
+    __shared__ float red[4][64];
+    const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + c;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (col < D) {
+        int b = r;
+        for (; b + 12 < blocks; b += 16) {
+            s0 += partials[(size_t)b * D + col];
+            s1 += partials[(size_t)(b + 4) * D + col];
+            s2 += partials[(size_t)(b + 8) * D + col];
+            s3 += partials[(size_t)(b + 12) * D + col];
+        }
+        for (; b < blocks; b += 4) s0 += partials[(size_t)b * D + col];
+    }
+    red[r][c] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (r == 0 && col < D) {
+        const float s = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+        dgamma[col] = accumulate ? dgamma[col] + s : s;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -240,20 +317,38 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ param, u
     const af32x4* g4 = (const af32x4*)grad;
     af32x4* m4 = (af32x4*)m;
     af32x4* v4 = (af32x4*)v;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
-        af32x4 p = p4[i], g = g4[i], mm = m4[i], vv = v4[i];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float pe = p[e], me = mm[e], ve = vv[e];
-            adamw_one(pe, g[e] * clip, me, ve, a);
-            p[e] = pe; mm[e] = me; vv[e] = ve;
+    // every tensor is touched exactly once: streaming (non-temporal) accesses, two independent
+    // 16-byte groups per thread and iteration
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < n4; i0 += 2 * stride) {
+        const int64_t i1 = i0 + stride;
+        const bool two = i1 < n4;
+        af32x4 p[2], g[2], mm[2], vv[2];
+        p[0] = __builtin_nontemporal_load(p4 + i0); g[0] = __builtin_nontemporal_load(g4 + i0);
+        mm[0] = __builtin_nontemporal_load(m4 + i0); vv[0] = __builtin_nontemporal_load(v4 + i0);
+        if (two) {
+            p[1] = __builtin_nontemporal_load(p4 + i1); g[1] = __builtin_nontemporal_load(g4 + i1);
+            mm[1] = __builtin_nontemporal_load(m4 + i1); vv[1] = __builtin_nontemporal_load(v4 + i1);
         }
-        p4[i] = p; m4[i] = mm; v4[i] = vv;
-        if (param_bf16) {
-            union { __bf16 h[4]; unsigned long long u; } cv;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)p[e];
-            *(unsigned long long*)(param_bf16 + (i << 2)) = cv.u;
+        for (int k = 0; k < 2; ++k) {
+            if (k == 1 && !two) break;
+            const int64_t i = k == 0 ? i0 : i1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float pe = p[k][e], me = mm[k][e], ve = vv[k][e];
+                adamw_one(pe, g[k][e] * clip, me, ve, a);
+                p[k][e] = pe; mm[k][e] = me; vv[k][e] = ve;
+            }
+            __builtin_nontemporal_store(p[k], p4 + i);
+            __builtin_nontemporal_store(mm[k], m4 + i);
+            __builtin_nontemporal_store(vv[k], v4 + i);
+            if (param_bf16) {
+                union { __bf16 h[4]; unsigned long long u; } cv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)p[k][e];
+                *(unsigned long long*)(param_bf16 + (i << 2)) = cv.u;
+            }
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
@@ -292,8 +387,12 @@ int cce_rmsnorm_forward(const void* x, const void* gamma, int64_t N, int64_t D, 
     if (!norm_shape_ok(N, D)) return CCE_ERR_UNSUPPORTED;
     if (((uintptr_t)x | (uintptr_t)gamma | (uintptr_t)y) & 15) return CCE_ERR_INVALID;
     if ((uintptr_t)rstd & 3) return CCE_ERR_INVALID;
-    hipLaunchKernelGGL(rmsnorm_forward_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, (hipStream_t)stream_,
-                       (const uint16_t*)x, (const uint16_t*)gamma, (int)N, (int)D, eps, (uint16_t*)y, rstd);
+    const dim3 grid((unsigned)((N + 3) / 4));
+    hipStream_t stream = (hipStream_t)stream_;
+#define CCE_NORM_FWD(CH) hipLaunchKernelGGL(rmsnorm_forward_kernel<CH>, grid, dim3(256), 0, stream, \
+        (const uint16_t*)x, (const uint16_t*)gamma, (int)N, (int)D, eps, (uint16_t*)y, rstd)
+    if (D <= 1024) CCE_NORM_FWD(2); else if (D <= 2048) CCE_NORM_FWD(4); else if (D <= 4096) CCE_NORM_FWD(8); else CCE_NORM_FWD(16);
+#undef CCE_NORM_FWD
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
@@ -310,10 +409,11 @@ int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, co
     hipStream_t stream = (hipStream_t)stream_;
     const int blocks = norm_backward_blocks(N);
     float* partials = (float*)workspace;
-    hipLaunchKernelGGL(rmsnorm_backward_kernel, dim3(blocks), dim3(256), 0, stream,
-                       (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D,
-                       (uint16_t*)dx, partials);
-    hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, stream,
+#define CCE_NORM_BWD(CH) hipLaunchKernelGGL(rmsnorm_backward_kernel<CH>, dim3(blocks), dim3(256), 0, stream, \
+        (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D, (uint16_t*)dx, partials)
+    if (D <= 1024) CCE_NORM_BWD(2); else if (D <= 2048) CCE_NORM_BWD(4); else if (D <= 4096) CCE_NORM_BWD(8); else CCE_NORM_BWD(16);
+#undef CCE_NORM_BWD
+    hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 63) / 64)), dim3(256), 0, stream,
                        (const float*)partials, blocks, (int)D, dgamma, accumulate_dgamma ? 1 : 0);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
@@ -357,7 +457,7 @@ int cce_adamw_step(float* param, void* param_bf16, const float* grad, float* m, 
     a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
     a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
     const int64_t want = ((n >> 2) + 255) / 256;
-    const int blocks = (int)(want < 1 ? 1 : (want < 8192 ? want : 8192));
+    const int blocks = (int)(want < 1 ? 1 : (want < 4096 ? want : 4096));
     hipLaunchKernelGGL(adamw_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream_,
                        param, (uint16_t*)param_bf16, grad, m, v, n, a, clip_coef);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
