@@ -457,7 +457,7 @@ int cce_adamw_step(float* param, void* param_bf16, const float* grad, float* m, 
     a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
     a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
     const int64_t want = ((n >> 2) + 255) / 256;
-    const int blocks = (int)(want < 1 ? 1 : (want < 4096 ? want : 4096));
+    const int blocks = (int)(want < 1 ? 1 : (want < 131072 ? want : 131072));
     hipLaunchKernelGGL(adamw_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream_,
                        param, (uint16_t*)param_bf16, grad, m, v, n, a, clip_coef);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;

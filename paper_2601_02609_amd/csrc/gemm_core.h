@@ -275,11 +275,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
         CCE_LDS char* cur = smem + cur_s * Cfg::kStage;
         const int nxt_s = (cur_s + 1 == S) ? 0 : cur_s + 1;
         CCE_LDS char* nxt = smem + nxt_s * Cfg::kStage;
-#ifdef CCE_DBG_SKIP_GLOBAL
-        const bool more = false;
-#else
         const bool more = kt + S - 1 < KT;
-#endif
         if (more) {
             const int ld_s = (cur_s == 0) ? S - 1 : cur_s - 1;   // stage of slice kt - 1, free again
             A.issue(smem + ld_s * Cfg::kStage, (kt + S - 1) * kBK);
@@ -288,32 +284,19 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
 #pragma unroll
         for (int kk = 0; kk < SPS; ++kk) {
             const int c = kk & 1, n = c ^ 1;
-#ifdef CCE_DBG_SKIP_LDS
-            if (false) {
-#else
             if (kk < SPS - 1) {
-#endif
 #pragma unroll
                 for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = fa.load(cur, bm, kk + 1);
 #pragma unroll
                 for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = fb.load(cur + Cfg::kAStage, bn, kk + 1);
             } else {
                 // slice kt + 1 must have landed; younger slices may still be in flight
-#ifndef CCE_DBG_SKIP_BARRIER
                 if (more) barrier_pending_loads<kAhead>();
                 else barrier_pending_loads<0>();
-#endif
-#ifndef CCE_DBG_SKIP_LDS
 #pragma unroll
                 for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = fa.load(nxt, bm, 0);
 #pragma unroll
                 for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = fb.load(nxt + Cfg::kAStage, bn, 0);
-#else
-#pragma unroll
-                for (int bm = 0; bm < Cfg::TM; ++bm) af[n][bm] = af[c][bm];
-#pragma unroll
-                for (int bn = 0; bn < Cfg::TN; ++bn) bfr[n][bn] = bfr[c][bn];
-#endif
             }
 #pragma unroll
             for (int bm = 0; bm < Cfg::TM; ++bm)
