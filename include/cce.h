@@ -22,7 +22,10 @@
  *     dW [V, D].  Pointers must be 16-byte aligned.
  *   - bf16 tensors are raw 16-bit patterns (`void*`); fp32 tensors are `float*`.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
- *     work is enqueued on it, in order.
+ *     work is enqueued on it, in order.  cce_forward[_ex] and cce_backward[_ex] consist of
+ *     kernel launches only (no memset, copy, allocation or synchronisation), so a stream
+ *     under HIP graph capture may call them once the library has been used once on the
+ *     device outside a capture (the first call raises the kernels' LDS limit).
  *   - D must be a positive multiple of 64 (the K granule of the MFMA main loop);
  *     N, V >= 1 are otherwise arbitrary (ragged tiles are masked).
  *   - A row whose label equals `ignore_index` yields loss = lse = 0, a zero dHidden

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     // Work index -> (token tile, vocabulary split).  The 32 workgroups that share an XCD (and
     // its 4 MB L2) take a panel of 4 token tiles x all splits: per K slice they touch 4 H
     // tiles + S W tiles instead of 32 + 1, which is what keeps most operand fetches in L2.
-    const int lin = xcd_linear_id(blockIdx.x, gridDim.x);
+    const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
     int tt, s;
     group_map(lin, TT, S, 4, tt, s);
     const int vt0 = (int)((int64_t)s * VT / S), vt1 = (int)((int64_t)(s + 1) * VT / S);
@@ -779,6 +779,25 @@ static bool allow_big_lds(K kernel, int bytes) {
     return hip_ok(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
 }
 
+constexpr int kGradTileLds = (256 * kGRowBytes + 256 > TileBig::kLdsBytes) ? 256 * kGRowBytes + 256 : TileBig::kLdsBytes;
+
+// The MFMA kernels use more dynamic LDS than the default limit: raise it once per device
+// (not per call, so that the compute calls consist of kernel launches only).
+static bool ensure_kernel_attributes() {
+    static bool done[64] = {};
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return false;
+    if (dev < 0 || dev >= 64) return false;
+    if (done[dev]) return true;
+    if (!allow_big_lds(lse_partial_kernel<false>, TileBig::kLdsBytes)) return false;
+    if (!allow_big_lds(lse_partial_kernel<true>, TileBig::kLdsBytes)) return false;
+    if (!allow_big_lds(grad_tile_kernel, kGradTileLds)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return false;
+    done[dev] = true;
+    return true;
+}
+
 }  // namespace cce
 
 using namespace cce;
@@ -833,8 +852,7 @@ int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels
     const bool smooth = label_smoothing != 0.f;
     float* sumz = smooth ? (float*)(ws + p.off_sumz) : (float*)nullptr;
 
-    if (!allow_big_lds(lse_partial_kernel<false>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
-    if (!allow_big_lds(lse_partial_kernel<true>, TileBig::kLdsBytes)) return CCE_ERR_HIP;
+    if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     {
         ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
@@ -874,6 +892,7 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
     if (rc != CCE_OK) return rc;
+    if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
     float* dhacc = (float*)(ws + p.off_dhacc);
@@ -883,11 +902,7 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
     if (!dloss)
         hipLaunchKernelGGL(mean_scale_kernel, dim3(1), dim3(1024), 0, stream,
                            labels, (int)N, (int)V, ignore_index, grad_scale, mean_scale);
-
-    const int grad_lds = (256 * kGRowBytes + 256 > TileBig::kLdsBytes) ? 256 * kGRowBytes + 256 : TileBig::kLdsBytes;
-    if (!allow_big_lds(grad_tile_kernel, grad_lds)) return CCE_ERR_HIP;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return CCE_ERR_HIP;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return CCE_ERR_HIP;
+    const int grad_lds = kGradTileLds;
 
     const GemmTile gt = gemm_tile_for(D);
     const int d_tiles = (int)((D + gt.bn - 1) / gt.bn);
