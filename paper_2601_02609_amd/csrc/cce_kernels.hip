@@ -369,7 +369,12 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     CCE_LDS unsigned char* live_flags = (CCE_LDS unsigned char*)(smem + 256 * kGRowBytes);
     if (threadIdx.x < Cfg::BN) live_flags[threadIdx.x] = row_live ? 1 : 0;
 
-    // epilogue: softmax gradient, bf16, stage to LDS [token][vocab]
+    // Epilogue: softmax gradient, bf16, staged in LDS as [token][vocab] and stored with
+    // full 512-byte rows.  Done in TN phases (the 32 token columns per wavefront of block
+    // bn): the global stores of one phase drain while the next phase is computed, and the
+    // barriers wait for LDS traffic only.
+    const bool ragged = vt0 + Cfg::BM > V;                  // only the last vocabulary tile needs column masking
+    const int chunk = threadIdx.x & 31;
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int col = acc_col<Cfg>(bn);
@@ -391,21 +396,23 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
                     for (int e = 0; e < 4; ++e) g[e] -= (rrel + e == yrel) ? ch : 0.f;
                 }
                 const int vrow = wm * (Cfg::TM * 32) + rrel;            // row inside the tile
-                const int vglob = vt0 + vrow;
+                if (ragged) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) g[e] = (vt0 + vrow + e < V) ? g[e] : 0.f;
+                }
                 union { __bf16 h[4]; u32x2 u; } pk;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)((vglob + e < V) ? g[e] : 0.f);
+                for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)g[e];
                 *(CCE_LDS u32x2*)(smem + col * kGRowBytes + vrow * 2) = pk.u;
             }
         }
-    }
-    __syncthreads();
-    // coalesced store: thread -> (row = t / 32 + 16 j, 16-byte chunk = t % 32)
-    {
-        const int chunk = threadIdx.x & 31;
-#pragma unroll 4
-        for (int j = 0; j < 16; ++j) {
-            const int row = (threadIdx.x >> 5) + 16 * j;
+        barrier_lds_only();
+        // rows of this phase: tokens 64 * wn + 32 * bn + (0..31) for the WN wavefront columns;
+        // thread -> (row index t / 32 + 16 j, 16-byte chunk t % 32)
+#pragma unroll
+        for (int j = 0; j < (Cfg::WN * 32) / 16; ++j) {
+            const int idx = (threadIdx.x >> 5) + 16 * j;
+            const int row = (idx >> 5) * (Cfg::TN * 32) + bn * 32 + (idx & 31);
             const bool live = live_flags[row] != 0;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (live) v = *(const CCE_LDS u32x4*)(smem + row * kGRowBytes + chunk * 16);
