@@ -94,3 +94,36 @@ def test_variant_argument_errors(B):
     for eps, lam in [(-0.1, 0.0), (1.0, 0.0), (0.0, -1.0), (0.0, float("nan"))]:
         with pytest.raises(B.CCEError):
             B.cce_forward_ex(H, W, y, IGN, label_smoothing=eps, z_loss=lam)
+
+
+def test_variants_at_the_headline_shape_sampled(B):
+    """Label smoothing + z-loss + mean reduction at N=8192, D=896, V=151936: loss / lse / dHidden on a
+    seeded sample of rows (each needs only its own row and the full vocabulary), the mean over all
+    rows from the oracle's closed relation to the plain loss on that sample, and the row-sum
+    property of the smoothed gradient on all of dW."""
+    w = I.make_config("qwen05b")
+    N, D, V = w.spec.N, w.spec.D, w.spec.V
+    eps, lam = 0.1, 1e-4
+    H, W, y = dev_inputs(w)
+    ws = B.alloc_workspace(N, D, V)
+    loss, lse, mean = B.cce_forward_ex(H, W, y, IGN, label_smoothing=eps, z_loss=lam, want_mean=True, workspace=ws)
+    dH, dW = B.cce_backward_ex(H, W, y, lse, None, IGN, grad_scale=1.0, label_smoothing=eps, z_loss=lam, workspace=ws)
+    torch.cuda.synchronize()
+    g_loss, g_lse = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, N - 1, 255, 256], rng.choice(N, 28, replace=False)])).astype(np.int64)
+    print(f"[variants] headline shape: oracle on {rows.size} rows", flush=True)
+    o_loss, o_lse = O.forward(w.hidden[rows], w.weight, w.labels[rows], IGN, label_smoothing=eps, z_loss=lam)
+    dl = np.full(rows.size, 1.0 / w.n_valid, dtype=np.float32)
+    o_dH, _ = O.backward(w.hidden[rows], w.weight, w.labels[rows], dl, IGN, label_smoothing=eps, z_loss=lam)
+    assert np.abs(g_loss[rows] - o_loss).max() <= LOSS_ATOL and np.abs(g_lse[rows] - o_lse).max() <= LOSS_ATOL
+    assert rel_fro(bf16_host(dH[torch.from_numpy(rows).cuda()]), o_dH) <= GRAD_RTOL
+    # the in-library mean is the mean of the per-token losses it returned
+    assert abs(float(mean.item()) - g_loss.sum() / w.n_valid) <= 1e-4
+    # rows of the smoothed gradient sum to 2 lambda lse_i dloss_i (zero without the z-loss), hence
+    # sum_v dW[v, :] = sum_i 2 lambda lse_i / n_valid * h_i
+    Hf = I.bf16_bits_to_f32(w.hidden).astype(np.float64)
+    want = (2 * lam * g_lse[:, None] / w.n_valid * Hf).sum(axis=0)
+    got = dW.double().sum(dim=0).cpu().numpy()
+    scale = dW.double().abs().sum(dim=0).max().item()
+    assert np.abs(got - want).max() <= 2e-3 * scale
