@@ -52,8 +52,8 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path shards over tokens or vocabulary "
-              "as described in DESIGN.md, but no multi-GPU code is part of it); use --gpus 1",
+        print("bench.py: this build runs on ONE GPU only (the path would shard over tokens or over the "
+              "vocabulary, but no multi-GPU code is part of it); use --gpus 1",
               file=sys.stderr)
         return 2
 
