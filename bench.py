@@ -183,6 +183,16 @@ def main() -> int:
                "frac_of_8TBps": round(aux_bytes[k] / aux_us[k] * 1e-3 / 8000.0, 3)} for k in aux_us}
     del master, mom, var, Wcopy
 
+    # what the peak is divided by: the nominal figure, the one the device properties give
+    # (compute units x 4096 flop/clock x clock), and a register-only MFMA loop on this device
+    cus, khz = B.device_info()
+    peak_info = {
+        "nominal_tflops": MFMA_BF16_PEAK_TFLOPS,
+        "from_device_properties_tflops": round(cus * 4096 * khz * 1e3 / 1e12, 1),
+        "compute_units": cus, "clock_mhz": khz // 1000,
+        "register_only_mfma_loop_tflops": round(B.mfma_probe_tflops(), 1),
+    }
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import cce_oracle as O     # baseline leg only; never on the product path
@@ -214,7 +224,7 @@ def main() -> int:
         "workspace_pct_of_logits": round(100.0 * ws.numel() / B.materialised_logit_bytes(N, V), 3),
         "backward_tiling_256": list(B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
-        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux,
+        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "mfma_peak": peak_info,
     }
     print(json.dumps(out))
     return 0

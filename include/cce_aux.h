@@ -95,6 +95,20 @@ int cce_adamw_step(float* param, void* param_bf16, const float* grad, float* m, 
                    float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
                    const float* clip_coef, void* stream);
 
+/*
+ * Measurement aid (not part of the paper's method): launches `workgroups` workgroups of 8
+ * wavefronts that each issue iters x 8 v_mfma_f32_32x32x16_bf16 on register operands only --
+ * workgroups * 8 * iters * 8 * 32768 flop in all.  Timed by the caller (events on `stream`), it
+ * gives the MFMA rate the device sustains with nothing else in the way, next to the nominal
+ * peak.  `sink` is a device fp32 [1] that is never written in practice.
+ */
+int cce_mfma_probe(int workgroups, int iters, float* sink, void* stream);
+
+/* Compute units and peak shader clock (kHz) of the current device, from the HIP device
+ * attributes: compute units x 4096 bf16 flop per clock x clock is the nominal dense MFMA peak.
+ * Both outputs are host ints. */
+int cce_device_info(int* compute_units, int* clock_khz);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,6 +29,7 @@ EXPORTED_SYMBOLS = [
     # include/cce_aux.h
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
     "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
+    "cce_mfma_probe", "cce_device_info",
 ]
 KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
@@ -98,6 +99,10 @@ def lib() -> ctypes.CDLL:
     L.cce_clip_coef.argtypes = [vp, f32, f32, vp, vp]
     L.cce_adamw_step.restype = ctypes.c_int
     L.cce_adamw_step.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i64, vp, vp]
+    L.cce_device_info.restype = ctypes.c_int
+    L.cce_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    L.cce_mfma_probe.restype = ctypes.c_int
+    L.cce_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
     _lib = L
     return L
 
@@ -395,3 +400,25 @@ def cce_adamw_step(param: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: 
                              grad.data_ptr(), m.data_ptr(), v.data_ptr(), n, lr, beta1, beta2, eps, weight_decay,
                              step, clip_coef.data_ptr() if clip_coef is not None else None,
                              _stream_ptr(stream)), "cce_adamw_step")
+
+
+def mfma_probe_tflops(workgroups: int = 2048, iters: int = 4000) -> float:
+    """TFLOP/s of a register-only bf16 MFMA loop on the current device (measurement aid)."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    s = _stream_ptr(None)
+    _rc(lib().cce_mfma_probe(workgroups, 10, sink.data_ptr(), s), "cce_mfma_probe")
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    _rc(lib().cce_mfma_probe(workgroups, iters, sink.data_ptr(), s), "cce_mfma_probe")
+    b.record()
+    torch.cuda.synchronize()
+    flops = float(workgroups) * 8 * iters * 8 * 32768
+    return flops / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
+def device_info() -> Tuple[int, int]:
+    """(compute units, peak shader clock in kHz) of the current device."""
+    cu, khz = ctypes.c_int(0), ctypes.c_int(0)
+    _rc(lib().cce_device_info(ctypes.byref(cu), ctypes.byref(khz)), "cce_device_info")
+    return int(cu.value), int(khz.value)

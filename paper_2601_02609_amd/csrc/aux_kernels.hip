@@ -360,6 +360,38 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ param, u
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Measurement aid: a register-only MFMA loop (no LDS, no global memory), the rate the matrix
+// cores sustain when nothing else is in the way.  Eight wavefronts per workgroup, eight
+// independent 32x32 accumulators per wavefront; the operands are lane-dependent constants.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 abf16x8;
+typedef __attribute__((ext_vector_type(16))) float af32x16;
+
+__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float seed, float* __restrict__ sink) {
+    abf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(seed + 0.001f * (float)((threadIdx.x * 8 + e) % 61));
+        b[e] = (__bf16)(seed - 0.002f * (float)((threadIdx.x * 8 + e) % 53));
+    }
+    af32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    if (t == 12345.678f) sink[0] = t;                 // keeps the loop alive; never true in practice
+}
+
 static bool norm_shape_ok(int64_t N, int64_t D) {
     return N > 0 && D > 0 && D % 64 == 0 && D <= (int64_t)kNormMaxChunks * 512 && N <= ((int64_t)1 << 30);
 }
@@ -439,6 +471,22 @@ int cce_grad_sumsq(const float* grad, int64_t n, double* sumsq, int accumulate,
 int cce_clip_coef(const double* sumsq, float max_norm, float eps_norm, float* clip_coef, void* stream_) {
     if (!sumsq || !clip_coef || !(max_norm > 0.f) || !(eps_norm >= 0.f)) return CCE_ERR_INVALID;
     hipLaunchKernelGGL(clip_coef_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream_, sumsq, max_norm, eps_norm, clip_coef);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_device_info(int* compute_units, int* clock_khz) {
+    if (!compute_units || !clock_khz) return CCE_ERR_INVALID;
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return CCE_ERR_HIP;
+    if (!hip_ok(hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, dev))) return CCE_ERR_HIP;
+    if (!hip_ok(hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev))) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_mfma_probe(int workgroups, int iters, float* sink, void* stream_) {
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || !sink) return CCE_ERR_INVALID;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream_, iters, 0.5f, sink);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
