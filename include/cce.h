@@ -157,7 +157,9 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
  * choice, which stays inside the workspace budget (1 % of the materialised logits, at
  * least 48 MiB).  The chunking is a free parameter of the chunk-level backward
  * algorithm: results agree across tilings up to fp32 summation order.  Host state only;
- * not thread safe.  Returns CCE_ERR_INVALID for negative values or when only one is 0.
+ * not thread safe.  Returns CCE_ERR_INVALID for negative values or when only one is 0.  A forced
+ * tiling whose gradient chunk (rows x columns x 2 bytes) would reach 4 GiB makes the calls that
+ * use it fail with CCE_ERR_INVALID (cce_workspace_bytes returns 0).
  */
 int cce_set_backward_tiling(int row_tiles, int vocab_tiles);
 

@@ -757,6 +757,8 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     }
     p->Nb = (int64_t)best_a * 256;
     p->Vc = (int64_t)best_b * 256;
+    // the gradient chunk is addressed with 32-bit byte offsets (only a forced tiling can get here)
+    if (p->Nb * p->Vc * 2 >= ((int64_t)1 << 32)) return false;
     p->off_status = 0;
     p->off_partials = 256;
     p->off_sumz = p->off_partials + md_bytes;

@@ -61,3 +61,18 @@ def test_workspace_is_small_and_independent_of_NV(L):
     # O(N*D + tile): doubling V must not double the workspace beyond the 1 % budget rule
     for (n, d, v) in [(16384, 2048, 151936), (32768, 3584, 151936)]:
         assert binding.workspace_bytes(n, d, v) <= 0.01 * binding.materialised_logit_bytes(n, v)
+
+
+def test_forced_tiling_is_bounded(L):
+    """A forced tiling whose gradient chunk would need more than 32-bit byte offsets is refused."""
+    try:
+        binding.set_backward_tiling(128, 594)
+        assert binding.workspace_bytes(32768, 3584, 151936) == 0
+        binding.set_backward_tiling(2, 3)
+        assert binding.get_backward_tiling(8192, 896, 151936) == (2, 3)
+        assert binding.workspace_bytes(8192, 896, 151936) > 0
+    finally:
+        binding.set_backward_tiling(0, 0)
+    assert binding.get_backward_tiling(8192, 896, 151936) == (16, 16)
+    with pytest.raises(binding.CCEError):
+        binding.set_backward_tiling(3, 0)
