@@ -30,6 +30,8 @@ EXPORTED_SYMBOLS = [
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
     "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
     "cce_mfma_probe", "cce_device_info",
+    # include/cce_shard.h
+    "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
 ]
 KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
@@ -103,6 +105,13 @@ def lib() -> ctypes.CDLL:
     L.cce_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     L.cce_mfma_probe.restype = ctypes.c_int
     L.cce_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+    L.cce_shard_forward.restype = ctypes.c_int
+    L.cce_shard_forward.argtypes = [vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, vp, vp, sz, vp]
+    L.cce_shard_merge.restype = ctypes.c_int
+    L.cce_shard_merge.argtypes = [vp, ctypes.c_int, vp, i64, i64, i32, f32, f32, vp, vp, vp, vp, vp]
+    L.cce_shard_backward.restype = ctypes.c_int
+    L.cce_shard_backward.argtypes = [vp, vp, vp, vp, vp, f32, i64, i64, i64, i64, i64, i32, f32, f32,
+                                     vp, vp, ctypes.c_int, vp, sz, vp]
     _lib = L
     return L
 
@@ -422,3 +431,82 @@ def device_info() -> Tuple[int, int]:
     cu, khz = ctypes.c_int(0), ctypes.c_int(0)
     _rc(lib().cce_device_info(ctypes.byref(cu), ctypes.byref(khz)), "cce_device_info")
     return int(cu.value), int(khz.value)
+
+
+# ---------------------------------------------------------------- include/cce_shard.h
+
+def cce_shard_forward(hidden: torch.Tensor, weight_shard: torch.Tensor, labels: torch.Tensor,
+                      vocab_offset: int, *, want_sumz: bool = False,
+                      stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Per-token (max, sum-exp, label logit, logit sum) of one vocabulary shard, fp32 [N, 4]."""
+    N, D = hidden.shape
+    Vs = weight_shard.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight_shard, torch.bfloat16, (Vs, D), "weight_shard")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, Vs, hidden.device)
+    if stats is None:
+        stats = torch.empty(N, 4, dtype=torch.float32, device=hidden.device)
+    _check(stats, torch.float32, (N, 4), "stats")
+    _rc(lib().cce_shard_forward(hidden.data_ptr(), weight_shard.data_ptr(), labels.data_ptr(), N, D, Vs,
+                                vocab_offset, 1 if want_sumz else 0, stats.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_shard_forward")
+    return stats
+
+
+def cce_shard_merge(stats: torch.Tensor, labels: torch.Tensor, V_total: int, ignore_index: int = -100, *,
+                    label_smoothing: float = 0.0, z_loss: float = 0.0, want_mean: bool = False,
+                    status: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None):
+    """(loss [N], lse [N], mean_loss [1] or None) from the stacked shard statistics [P, N, 4]."""
+    P, N, _ = stats.shape
+    _check(stats, torch.float32, (P, N, 4), "stats")
+    _check(labels, torch.int32, (N,), "labels")
+    if status is not None:
+        _check(status, torch.int32, (1,), "status")
+    loss = torch.empty(N, dtype=torch.float32, device=stats.device)
+    lse = torch.empty(N, dtype=torch.float32, device=stats.device)
+    mean = torch.empty(1, dtype=torch.float32, device=stats.device) if want_mean else None
+    _rc(lib().cce_shard_merge(stats.data_ptr(), P, labels.data_ptr(), N, V_total, ignore_index,
+                              label_smoothing, z_loss, loss.data_ptr(), lse.data_ptr(),
+                              mean.data_ptr() if mean is not None else None,
+                              status.data_ptr() if status is not None else None,
+                              _stream_ptr(stream)), "cce_shard_merge")
+    return loss, lse, mean
+
+
+def cce_shard_backward(hidden: torch.Tensor, weight_shard: torch.Tensor, labels: torch.Tensor,
+                       lse: torch.Tensor, dloss: Optional[torch.Tensor], vocab_offset: int, V_total: int,
+                       ignore_index: int = -100, *, grad_scale: float = 1.0,
+                       label_smoothing: float = 0.0, z_loss: float = 0.0,
+                       workspace: Optional[torch.Tensor] = None,
+                       d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                       accumulate_dw: bool = False,
+                       stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(partial dHidden bf16 [N, D], dW of the shard fp32 [Vs, D]) from the global lse."""
+    N, D = hidden.shape
+    Vs = weight_shard.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight_shard, torch.bfloat16, (Vs, D), "weight_shard")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    if dloss is not None:
+        _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, Vs, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(Vs, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (Vs, D), "d_weight")
+    _rc(lib().cce_shard_backward(hidden.data_ptr(), weight_shard.data_ptr(), labels.data_ptr(), lse.data_ptr(),
+                                 dloss.data_ptr() if dloss is not None else None, grad_scale,
+                                 N, D, Vs, vocab_offset, V_total, ignore_index, label_smoothing, z_loss,
+                                 d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_shard_backward")
+    return d_hidden, d_weight

@@ -12,7 +12,8 @@ LIB_PATH = os.path.join(PKG_DIR, "libcce.so")
 SOURCES = [os.path.join(CSRC, "cce_kernels.hip"), os.path.join(CSRC, "aux_kernels.hip")]
 HEADERS = [os.path.join(CSRC, "gemm_core.h"), os.path.join(CSRC, "host_util.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce.h"),
-           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_aux.h")]
+           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_aux.h"),
+           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_shard.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

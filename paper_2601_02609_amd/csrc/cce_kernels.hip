@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "../../include/cce.h"
+#include "../../include/cce_shard.h"
 #include "gemm_core.h"
 #include "host_util.h"
 
@@ -194,21 +195,27 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
 // ------------------------------------------------------------------------------------------
 // Forward finalisation: one wavefront per token.
 // ------------------------------------------------------------------------------------------
+// With `stats` (vocabulary-parallel share): W holds the rows [v_off, v_off + V) of the full
+// matrix; instead of a loss the kernel writes, for EVERY token, the shard's statistics
+// stats[tok] = (max logit, sum exp(z - max), label logit or 0 when the label lies in another
+// shard, sum of logits or 0) in natural units; labels are not judged here.
 __global__ __launch_bounds__(256) void finalize_kernel(
         const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, const int32_t* __restrict__ labels,
         const float2* __restrict__ partials, const float* __restrict__ partial_sumz,
         int N, int D, int V, int S, int32_t ignore_index, float label_smoothing, float z_loss,
-        float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status) {
+        float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status,
+        int v_off, float4* __restrict__ stats) {
     const int l = threadIdx.x & 63;
     const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tok >= N) return;
-    const int32_t y = labels[tok];
-    const bool in_range = (y >= 0 && y < V);
-    if (y == ignore_index || !in_range) {
+    const int64_t y_local = (int64_t)labels[tok] - v_off;
+    const int32_t y = (y_local >= 0 && y_local < V) ? (int32_t)y_local : -1;     // row of W, or none
+    const bool in_range = y >= 0;
+    if (!stats && (labels[tok] == ignore_index || !in_range)) {
         if (l == 0) {
             loss[tok] = 0.f;
             lse[tok] = 0.f;
-            if (y != ignore_index) atomicOr(status, CCE_STATUS_BAD_LABEL);
+            if (labels[tok] != ignore_index) atomicOr(status, CCE_STATUS_BAD_LABEL);
         }
         return;
     }
@@ -226,16 +233,18 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     }
     // label logit: fp32 dot product of the two bf16 rows
     const uint16_t* h = H + (size_t)tok * D;
-    const uint16_t* w = W + (size_t)y * D;
+    const uint16_t* w = W + (size_t)(in_range ? y : 0) * D;
     float zy = 0.f;
-    for (int k = l * 2; k < D; k += 128) {
+    for (int k = l * 2; in_range && k < D; k += 128) {
         const uint32_t hv = *(const uint32_t*)(h + k), wv = *(const uint32_t*)(w + k);
         zy = fmaf(__uint_as_float(hv << 16), __uint_as_float(wv << 16), zy);
         zy = fmaf(__uint_as_float(hv & 0xffff0000u), __uint_as_float(wv & 0xffff0000u), zy);
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) zy += __shfl_xor(zy, o);
-    if (l == 0) {
+    if (l == 0 && stats) {
+        stats[tok] = make_float4(m * kLn2, d, zy, sumz);
+    } else if (l == 0) {
         const float out = (m + fast_log2(d)) * kLn2;
         lse[tok] = out;
         // (1 - eps) (lse - z_y) + eps (lse - mean_v z_v) + lambda lse^2   (smoothed cross-entropy
@@ -245,6 +254,37 @@ __global__ __launch_bounds__(256) void finalize_kernel(
         if (z_loss != 0.f) t = fmaf(z_loss * out, out, t);
         loss[tok] = t;
     }
+}
+
+// Vocabulary-parallel merge: one thread per token folds the P shard statistics
+// stats[p * N + tok] = (m, d, z_y, sum z) in shard order with the online-softmax merge and
+// writes the same loss / lse as finalize_kernel does for the undivided vocabulary.
+__global__ __launch_bounds__(256) void shard_merge_kernel(
+        const float4* __restrict__ stats, int P, const int32_t* __restrict__ labels, int N, int V,
+        int32_t ignore_index, float label_smoothing, float z_loss,
+        float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status) {
+    const int tok = blockIdx.x * 256 + threadIdx.x;
+    if (tok >= N) return;
+    const int32_t y = labels[tok];
+    if (y == ignore_index || y < 0 || y >= V) {
+        loss[tok] = 0.f;
+        lse[tok] = 0.f;
+        if (y != ignore_index && status) atomicOr(status, CCE_STATUS_BAD_LABEL);
+        return;
+    }
+    float m = -INFINITY, d = 0.f, zy = 0.f, sumz = 0.f;
+    for (int p = 0; p < P; ++p) {
+        const float4 st = stats[(size_t)p * N + tok];
+        md_merge(m, d, st.x * kLog2e, st.y);
+        zy += st.z;
+        sumz += st.w;
+    }
+    const float out = (m + fast_log2(d)) * kLn2;
+    lse[tok] = out;
+    float t = out - zy;
+    if (label_smoothing != 0.f) t = (1.f - label_smoothing) * t + label_smoothing * (out - sumz / (float)V);
+    if (z_loss != 0.f) t = fmaf(z_loss * out, out, t);
+    loss[tok] = t;
 }
 
 __global__ void clear_status_kernel(int32_t* status) { if (threadIdx.x == 0) status[0] = 0; }
@@ -305,6 +345,8 @@ __global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict
 //   plain softmax - onehot of the CCE backward theorem; eps is the label-smoothing weight
 //   (smoothed cross-entropy definition), lambda the z-loss weight (z-loss gradient
 //   proposition).  dloss == nullptr selects mean reduction: dloss_i = *mean_scale for all i.
+// W may be a vocabulary shard: its V rows are the rows [v_off, v_off + V) of a V_total-row
+// matrix, labels index the full one (v_off = 0, V_total = V without sharding).
 // Same orientation as the forward (lane owns a token column).  The tile is staged in LDS as
 // [token][vocab] and written to the scratch chunk G (row-major [rows_pad][ldg], vocab
 // contiguous) with full 512-byte rows.
@@ -315,7 +357,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
         const float* __restrict__ lse, const float* __restrict__ dloss, const float* __restrict__ mean_scale,
         int N, int D, int V, int32_t ignore_index, float label_smoothing, float z_loss,
         int row0, int n_row_tiles, int v0, int n_v_tiles,
-        uint16_t* __restrict__ G, int ldg) {
+        uint16_t* __restrict__ G, int ldg, int v_off, int V_total) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -341,12 +383,14 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     int32_t col_y[Cfg::TN];
     float col_sp[Cfg::TN], col_ch[Cfg::TN], col_ncs[Cfg::TN], col_nl2[Cfg::TN];
     const float uniform_dl = dloss ? 0.f : mean_scale[0];
-    const float eps_over_v = label_smoothing / (float)V;
+    const float eps_over_v = label_smoothing / (float)V_total;
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int tok = tok0 + acc_col<Cfg>(bn);
         const bool tok_ok = tok < N;
-        col_y[bn] = tok_ok ? labels[tok] : -1;
+        // label as a row of W (W holds the rows [v_off, v_off + V) of a V_total-row matrix)
+        const int64_t y_local = tok_ok ? (int64_t)labels[tok] - v_off : -1;
+        col_y[bn] = (y_local >= 0 && y_local < V) ? (int32_t)y_local : -1;
         const float dl = tok_ok ? (dloss ? dloss[tok] : uniform_dl) : 0.f;
         const float ls = tok_ok ? lse[tok] : 0.f;
         col_sp[bn] = dl * fmaf(2.f * z_loss, ls, 1.f);      // factor of the softmax term
@@ -357,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     bool row_live = false;
     if (threadIdx.x < Cfg::BN && tok0 + (int)threadIdx.x < N) {
         const int32_t y = labels[tok0 + threadIdx.x];
-        row_live = (y != ignore_index) && (y >= 0) && (y < V);
+        row_live = (y != ignore_index) && (y >= 0) && (y < V_total);
     }
 
     OperandTile<true, Cfg::BM> Aop;
@@ -843,22 +887,28 @@ static bool variant_ok(float label_smoothing, float z_loss) {
     return label_smoothing >= 0.f && label_smoothing < 1.f && z_loss >= 0.f && isfinite(z_loss);
 }
 
-int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels,
-                   int64_t N, int64_t D, int64_t V, int32_t ignore_index,
-                   float label_smoothing, float z_loss,
-                   float* loss, float* lse, float* mean_loss,
-                   void* workspace, size_t workspace_bytes, void* stream_) {
+// Forward over the V rows of `weight`, which are the rows [v_off, v_off + V) of the full
+// matrix.  With `stats` the per-token shard statistics are written instead of loss / lse
+// (`smooth` then says whether the logit sums are wanted).
+static int forward_impl(const void* hidden, const void* weight, const int32_t* labels,
+                        int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                        float label_smoothing, float z_loss,
+                        float* loss, float* lse, float* mean_loss,
+                        int64_t v_off, float* stats, bool want_sumz,
+                        void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
-    if (!loss || !lse) return CCE_ERR_INVALID;
+    if (!stats && (!loss || !lse)) return CCE_ERR_INVALID;
     if (((uintptr_t)loss | (uintptr_t)lse | (uintptr_t)mean_loss) & 3) return CCE_ERR_INVALID;
+    if ((uintptr_t)stats & 15) return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
+    if (v_off < 0 || v_off > (1 << 30)) return CCE_ERR_INVALID;
     int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
     if (rc != CCE_OK) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
     int32_t* status = (int32_t*)(ws + p.off_status);
     float2* partials = (float2*)(ws + p.off_partials);
-    const bool smooth = label_smoothing != 0.f;
+    const bool smooth = stats ? want_sumz : label_smoothing != 0.f;
     float* sumz = smooth ? (float*)(ws + p.off_sumz) : (float*)nullptr;
 
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
@@ -874,10 +924,47 @@ int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels
     }
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
                        (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials, (const float*)sumz,
-                       (int)N, (int)D, (int)V, p.S, ignore_index, label_smoothing, z_loss, loss, lse, status);
-    if (mean_loss)
+                       (int)N, (int)D, (int)V, p.S, ignore_index, label_smoothing, z_loss, loss, lse, status,
+                       (int)v_off, (float4*)stats);
+    if (mean_loss && !stats)
         hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
                            (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                   int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                   float label_smoothing, float z_loss,
+                   float* loss, float* lse, float* mean_loss,
+                   void* workspace, size_t workspace_bytes, void* stream_) {
+    return forward_impl(hidden, weight, labels, N, D, V, ignore_index, label_smoothing, z_loss,
+                        loss, lse, mean_loss, 0, nullptr, false, workspace, workspace_bytes, stream_);
+}
+
+int cce_shard_forward(const void* hidden, const void* weight_shard, const int32_t* labels,
+                      int64_t N, int64_t D, int64_t Vs, int64_t vocab_offset, int want_sumz,
+                      float* stats, void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!stats) return CCE_ERR_INVALID;
+    return forward_impl(hidden, weight_shard, labels, N, D, Vs, -1, 0.f, 0.f, nullptr, nullptr, nullptr,
+                        vocab_offset, stats, want_sumz != 0, workspace, workspace_bytes, stream_);
+}
+
+int cce_shard_merge(const float* stats, int P, const int32_t* labels, int64_t N, int64_t V_total,
+                    int32_t ignore_index, float label_smoothing, float z_loss,
+                    float* loss, float* lse, float* mean_loss, int32_t* status, void* stream_) {
+    if (!stats || !labels || !loss || !lse) return CCE_ERR_INVALID;
+    if (P <= 0 || P > 4096 || N <= 0 || N > (1 << 30) || V_total <= 0 || V_total > (1 << 30)) return CCE_ERR_INVALID;
+    if (((uintptr_t)stats & 15) || (((uintptr_t)loss | (uintptr_t)lse | (uintptr_t)mean_loss | (uintptr_t)status | (uintptr_t)labels) & 3))
+        return CCE_ERR_INVALID;
+    if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
+    hipStream_t stream = (hipStream_t)stream_;
+    hipLaunchKernelGGL(shard_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, stream,
+                       (const float4*)stats, P, labels, (int)N, (int)V_total, ignore_index, label_smoothing, z_loss,
+                       loss, lse, status);
+    if (mean_loss)
+        hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
+                           (const float*)loss, labels, (int)N, (int)V_total, ignore_index, mean_loss);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
@@ -889,16 +976,19 @@ int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
                           workspace, workspace_bytes, stream_);
 }
 
-int cce_backward_ex(const void* hidden, const void* weight, const int32_t* labels,
-                    const float* lse, const float* dloss, float grad_scale,
-                    int64_t N, int64_t D, int64_t V, int32_t ignore_index,
-                    float label_smoothing, float z_loss,
-                    void* dHidden, float* dW, int accumulate_dW,
-                    void* workspace, size_t workspace_bytes, void* stream_) {
+// Backward over the V rows of `weight`, which are the rows [v_off, v_off + V) of a matrix of
+// V_total rows that `labels`, label smoothing and the validity of a row refer to.
+static int backward_impl(const void* hidden, const void* weight, const int32_t* labels,
+                         const float* lse, const float* dloss, float grad_scale,
+                         int64_t N, int64_t D, int64_t V, int64_t v_off, int64_t V_total, int32_t ignore_index,
+                         float label_smoothing, float z_loss,
+                         void* dHidden, float* dW, int accumulate_dW,
+                         void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
     if (!lse || !dHidden || !dW) return CCE_ERR_INVALID;
     if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
+    if (v_off < 0 || V_total > (1 << 30) || v_off + V > V_total) return CCE_ERR_INVALID;
     int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
     if (rc != CCE_OK) return rc;
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
@@ -910,7 +1000,7 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
     float* mean_scale = (float*)(ws + p.off_status + 64);
     if (!dloss)
         hipLaunchKernelGGL(mean_scale_kernel, dim3(1), dim3(1024), 0, stream,
-                           labels, (int)N, (int)V, ignore_index, grad_scale, mean_scale);
+                           labels, (int)N, (int)V_total, ignore_index, grad_scale, mean_scale);
     const int grad_lds = kGradTileLds;
 
     const GemmTile gt = gemm_tile_for(D);
@@ -940,7 +1030,7 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
             hipLaunchKernelGGL(grad_tile_kernel, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
                                hidden, weight, labels, lse, dloss, (const float*)mean_scale,
                                (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
-                               (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg);
+                               (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total);
         }
         // 2. both contractions in one launch
         // dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
@@ -976,6 +1066,27 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
+}
+
+int cce_backward_ex(const void* hidden, const void* weight, const int32_t* labels,
+                    const float* lse, const float* dloss, float grad_scale,
+                    int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                    float label_smoothing, float z_loss,
+                    void* dHidden, float* dW, int accumulate_dW,
+                    void* workspace, size_t workspace_bytes, void* stream_) {
+    return backward_impl(hidden, weight, labels, lse, dloss, grad_scale, N, D, V, 0, V, ignore_index,
+                         label_smoothing, z_loss, dHidden, dW, accumulate_dW, workspace, workspace_bytes, stream_);
+}
+
+int cce_shard_backward(const void* hidden, const void* weight_shard, const int32_t* labels,
+                       const float* lse, const float* dloss, float grad_scale,
+                       int64_t N, int64_t D, int64_t Vs, int64_t vocab_offset, int64_t V_total,
+                       int32_t ignore_index, float label_smoothing, float z_loss,
+                       void* dHidden_partial, float* dW_shard, int accumulate_dW,
+                       void* workspace, size_t workspace_bytes, void* stream_) {
+    return backward_impl(hidden, weight_shard, labels, lse, dloss, grad_scale, N, D, Vs, vocab_offset, V_total,
+                         ignore_index, label_smoothing, z_loss, dHidden_partial, dW_shard, accumulate_dW,
+                         workspace, workspace_bytes, stream_);
 }
 
 int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
