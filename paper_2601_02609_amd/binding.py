@@ -32,6 +32,8 @@ EXPORTED_SYMBOLS = [
     "cce_mfma_probe", "cce_device_info",
     # include/cce_shard.h
     "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
+    # include/cce_fp8.h
+    "cce_fp8_scale_bytes", "cce_quantize_e4m3", "cce_fp8_forward", "cce_fp8_backward",
 ]
 KERNEL_FAMILIES = ["lse_partial_kernel", "grad_tile_kernel", "grad_gemm_kernel"]
 
@@ -112,6 +114,14 @@ def lib() -> ctypes.CDLL:
     L.cce_shard_backward.restype = ctypes.c_int
     L.cce_shard_backward.argtypes = [vp, vp, vp, vp, vp, f32, i64, i64, i64, i64, i64, i32, f32, f32,
                                      vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_fp8_scale_bytes.restype = sz
+    L.cce_fp8_scale_bytes.argtypes = [i64, i64]
+    L.cce_quantize_e4m3.restype = ctypes.c_int
+    L.cce_quantize_e4m3.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.cce_fp8_forward.restype = ctypes.c_int
+    L.cce_fp8_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+    L.cce_fp8_backward.restype = ctypes.c_int
+    L.cce_fp8_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, ctypes.c_int, vp, sz, vp]
     _lib = L
     return L
 
@@ -509,4 +519,94 @@ def cce_shard_backward(hidden: torch.Tensor, weight_shard: torch.Tensor, labels:
                                  N, D, Vs, vocab_offset, V_total, ignore_index, label_smoothing, z_loss,
                                  d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_shard_backward")
+    return d_hidden, d_weight
+
+
+# ---------------------------------------------------------------- include/cce_fp8.h
+
+def fp8_scale_bytes(rows: int, D: int) -> int:
+    return int(lib().cce_fp8_scale_bytes(rows, D))
+
+
+def cce_quantize_e4m3(x: torch.Tensor, *, q: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(E4M3 codes uint8 [rows, D], block-scale exponent bytes uint8 [fp8_scale_bytes]) of bf16 x."""
+    rows, D = x.shape
+    _check(x, torch.bfloat16, (rows, D), "x")
+    n = fp8_scale_bytes(rows, D)
+    if n == 0:
+        raise CCEError(CCE_ERR_UNSUPPORTED, "cce_fp8_scale_bytes")
+    if q is None:
+        q = torch.empty(rows, D, dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(n, dtype=torch.uint8, device=x.device)
+    _check(q, torch.uint8, (rows, D), "q")
+    _check(scales, torch.uint8, (n,), "scales")
+    _rc(lib().cce_quantize_e4m3(x.data_ptr(), rows, D, q.data_ptr(), scales.data_ptr(), _stream_ptr(stream)),
+        "cce_quantize_e4m3")
+    return q, scales
+
+
+def cce_fp8_forward(hidden_q: torch.Tensor, hidden_scales: torch.Tensor, weight_q: torch.Tensor,
+                    weight_scales: torch.Tensor, labels: torch.Tensor, ignore_index: int = -100, *,
+                    workspace: Optional[torch.Tensor] = None, loss: Optional[torch.Tensor] = None,
+                    lse: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Per-token loss and log-sum-exp from the E4M3 operands."""
+    N, D = hidden_q.shape
+    V = weight_q.shape[0]
+    _check(hidden_q, torch.uint8, (N, D), "hidden_q")
+    _check(weight_q, torch.uint8, (V, D), "weight_q")
+    _check(hidden_scales, torch.uint8, (fp8_scale_bytes(N, D),), "hidden_scales")
+    _check(weight_scales, torch.uint8, (fp8_scale_bytes(V, D),), "weight_scales")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden_q.device)
+    if loss is None:
+        loss = torch.empty(N, dtype=torch.float32, device=hidden_q.device)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden_q.device)
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    _rc(lib().cce_fp8_forward(hidden_q.data_ptr(), hidden_scales.data_ptr(), weight_q.data_ptr(),
+                              weight_scales.data_ptr(), labels.data_ptr(), N, D, V, ignore_index,
+                              loss.data_ptr(), lse.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                              _stream_ptr(stream)), "cce_fp8_forward")
+    return loss, lse
+
+
+def cce_fp8_backward(hidden_q: torch.Tensor, hidden_scales: torch.Tensor, weight_q: torch.Tensor,
+                     weight_scales: torch.Tensor, hidden: torch.Tensor, weight: torch.Tensor,
+                     labels: torch.Tensor, lse: torch.Tensor, dloss: torch.Tensor, ignore_index: int = -100, *,
+                     workspace: Optional[torch.Tensor] = None,
+                     d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                     accumulate_dw: bool = False,
+                     stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """dHidden (bf16) and dW (fp32): gradient tiles from the E4M3 logits, contracted with the bf16 operands."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden_q, torch.uint8, (N, D), "hidden_q")
+    _check(weight_q, torch.uint8, (V, D), "weight_q")
+    _check(hidden_scales, torch.uint8, (fp8_scale_bytes(N, D),), "hidden_scales")
+    _check(weight_scales, torch.uint8, (fp8_scale_bytes(V, D),), "weight_scales")
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_workspace(N, D, V, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(V, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (V, D), "d_weight")
+    _rc(lib().cce_fp8_backward(hidden_q.data_ptr(), hidden_scales.data_ptr(), weight_q.data_ptr(),
+                               weight_scales.data_ptr(), hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(),
+                               lse.data_ptr(), dloss.data_ptr(), N, D, V, ignore_index,
+                               d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_fp8_backward")
     return d_hidden, d_weight

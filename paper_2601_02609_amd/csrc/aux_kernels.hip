@@ -10,6 +10,7 @@
 
 #include "../../include/cce.h"
 #include "../../include/cce_aux.h"
+#include "../../include/cce_fp8.h"
 #include "host_util.h"
 
 namespace cce {
@@ -392,6 +393,65 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float seed, 
     if (t == 12345.678f) sink[0] = t;                 // keeps the loop alive; never true in practice
 }
 
+// ------------------------------------------------------------------------------------------
+// Block-wise E4M3 quantisation (block-wise quantisation algorithm of the paper's FP8 section:
+// blocks of 128 elements, one scale each, clamp to +-448), with the scale rounded up to a
+// power of two so that the block-scaled MFMA can apply it: 2^e, e = ceil(log2(amax / 448)).
+// 16 lanes own one block (16 bytes of bf16 each); a block is 256 contiguous input bytes
+// because the row length is a multiple of 128.  amax = f x 2^p with 1 <= f < 2 gives
+// e = p - 8, plus one when f > 1.75 (448 = 1.75 x 2^8): integer work on the fp32 bit pattern.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) unsigned int q_u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int q_u32x2;
+
+// Scale layout: [D / 128][groups = ceil(rows / 128)][32][4] bytes, byte j of dword i of group g =
+// row 128 g + 32 j + i (the order the block-scaled MFMA loop reads them in); entries of rows
+// past the matrix in the last group are set to 127.
+__global__ __launch_bounds__(256) void quantize_e4m3_kernel(const uint16_t* __restrict__ x, int64_t n_blocks,
+                                                            int blocks_per_row, int rows, int groups,
+                                                            uint8_t* __restrict__ q, uint8_t* __restrict__ scales) {
+    const int64_t gb = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;       // 128-element block
+    const int j = threadIdx.x & 15;
+    const bool live = gb < n_blocks;
+    q_u32x4 v = {0u, 0u, 0u, 0u};
+    if (live) v = __builtin_nontemporal_load((const q_u32x4*)(x + gb * 128 + j * 8));
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(v[i] << 16);
+        f[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+#pragma unroll
+    for (int o = 1; o <= 8; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    const uint32_t ab = __float_as_uint(amax);
+    int e = (int)(ab >> 23) - 127 - 8 + ((ab & 0x7fffffu) > 0x600000u ? 1 : 0);
+    e = ab == 0u ? 0 : e;
+    e = e < -127 ? -127 : (e > 127 ? 127 : e);
+    int packed[2] = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = fminf(fmaxf(ldexpf(f[2 * i], -e), -448.f), 448.f);
+        const float b = fminf(fmaxf(ldexpf(f[2 * i + 1], -e), -448.f), 448.f);
+        if (i & 1) packed[i >> 1] = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, packed[i >> 1], true);
+        else packed[i >> 1] = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, packed[i >> 1], false);
+    }
+    if (!live) return;
+    const q_u32x2 out = {(unsigned)packed[0], (unsigned)packed[1]};
+    __builtin_nontemporal_store(out, (q_u32x2*)(q + gb * 128 + j * 8));
+    if (j == 0) {
+        const int row = (int)(gb / blocks_per_row);
+        const int kb = (int)(gb - (int64_t)row * blocks_per_row);
+        uint8_t* plane = scales + (size_t)kb * groups * 128;
+        plane[((size_t)(row >> 7) * 32 + (row & 31)) * 4 + ((row >> 5) & 3)] = (uint8_t)(e + 127);
+        if (row == rows - 1)
+            for (int r = rows; r < groups * 128; ++r)
+                plane[((size_t)(r >> 7) * 32 + (r & 31)) * 4 + ((r >> 5) & 3)] = 127;
+    }
+}
+
 static bool norm_shape_ok(int64_t N, int64_t D) {
     return N > 0 && D > 0 && D % 64 == 0 && D <= (int64_t)kNormMaxChunks * 512 && N <= ((int64_t)1 << 30);
 }
@@ -471,6 +531,25 @@ int cce_grad_sumsq(const float* grad, int64_t n, double* sumsq, int accumulate,
 int cce_clip_coef(const double* sumsq, float max_norm, float eps_norm, float* clip_coef, void* stream_) {
     if (!sumsq || !clip_coef || !(max_norm > 0.f) || !(eps_norm >= 0.f)) return CCE_ERR_INVALID;
     hipLaunchKernelGGL(clip_coef_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream_, sumsq, max_norm, eps_norm, clip_coef);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+size_t cce_fp8_scale_bytes(int64_t rows, int64_t D) {
+    if (rows <= 0 || D <= 0 || D % 128 != 0 || rows > ((int64_t)1 << 30)) return 0;
+    return (size_t)(D / 128) * (size_t)((rows + 127) / 128) * 128u;
+}
+
+int cce_quantize_e4m3(const void* x, int64_t rows, int64_t D, void* q, void* scales, void* stream_) {
+    if (!x || !q || !scales || rows <= 0 || D <= 0) return CCE_ERR_INVALID;
+    if (D % 128 != 0 || rows > ((int64_t)1 << 30) || rows * D >= ((int64_t)1 << 40)) return CCE_ERR_UNSUPPORTED;
+    if ((((uintptr_t)x | (uintptr_t)q) & 15) || ((uintptr_t)scales & 3)) return CCE_ERR_INVALID;
+    const int64_t n_blocks = rows * (D / 128);
+    const int64_t grid = (n_blocks * 16 + 255) / 256;
+    if (grid > 0x7fffffff) return CCE_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(quantize_e4m3_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream_,
+                       (const uint16_t*)x, n_blocks, (int)(D / 128), (int)rows, (int)((rows + 127) / 128),
+                       (uint8_t*)q, (uint8_t*)scales);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }

@@ -21,6 +21,7 @@
 
 #include "../../include/cce.h"
 #include "../../include/cce_shard.h"
+#include "../../include/cce_fp8.h"
 #include "gemm_core.h"
 #include "host_util.h"
 
@@ -81,11 +82,26 @@ __device__ __forceinline__ void md_merge(float& m, float& d, float m2, float d2)
 // ------------------------------------------------------------------------------------------
 // SUMZ (label smoothing only): the sum of a token's logits over the vocabulary split is carried
 // along as well, partial_sumz[token * S + split]; the smoothed loss needs their mean.
-template <bool SUMZ>
+// FP8: H and W are E4M3 bytes (row length D) with one scale-exponent byte per row and 128
+// columns in hscale / wscale (grouped layout, see ScaleGroup); the logit tile is then formed by the
+// block-scaled FP8 MFMA loop and everything after it is unchanged.
+struct Fp8Scales {
+    const void* hscale;
+    const void* wscale;
+    int hgroups, wgroups;       // ceil(rows / 128) of each matrix
+};
+
+// Exponent byte of (row, 128-block kb) in the grouped scale layout (see ScaleGroup).
+__device__ __forceinline__ int scale_byte(const void* scales, int groups, int row, int kb) {
+    const uint8_t* s = (const uint8_t*)scales;
+    return s[(((size_t)kb * groups + (row >> 7)) * 32 + (row & 31)) * 4 + ((row >> 5) & 3)];
+}
+
+template <bool SUMZ, bool FP8>
 __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
         const void* __restrict__ H, const void* __restrict__ W,
         int N, int D, int V, int TT, int VT, int S, float2* __restrict__ partials,
-        float* __restrict__ partial_sumz) {
+        float* __restrict__ partial_sumz, const Fp8Scales fp8) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -100,8 +116,12 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
     const int l = threadIdx.x & 63;
     const int wm = wave_m<Cfg>();
 
+    const int ld = FP8 ? D / 2 : D;               // row length in 2-byte units
     OperandTile<true, Cfg::BN> Bop;
-    Bop.init(H, D, tt * Cfg::BN, N, D);
+    Bop.init(H, ld, tt * Cfg::BN, N, ld);
+    ScaleGroup SB;
+    const int b_row0 = tt * Cfg::BN + wave_n<Cfg>() * (Cfg::TN * 32);      // this wavefront's first token
+    if (FP8) SB.init(fp8.hscale, fp8.hgroups, b_row0 >> 7);
 
     float run_m[Cfg::TN], run_d[Cfg::TN], run_z[Cfg::TN];
 #pragma unroll
@@ -117,8 +137,14 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
                 for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
 
         OperandTile<true, Cfg::BM> Aop;
-        Aop.init(W, D, vt * Cfg::BM, V, D);
-        gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+        Aop.init(W, ld, vt * Cfg::BM, V, ld);
+        if (FP8) {
+            ScaleGroup SA;
+            SA.init(fp8.wscale, fp8.wgroups, (vt * Cfg::BM + wm * (Cfg::TM * 32)) >> 7);
+            gemm_mainloop_fp8<Cfg>(acc, Aop, Bop, SA, SB, (b_row0 >> 6) & 1, D, smem);
+        } else {
+            gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+        }
 
         if ((vt + 1) * Cfg::BM > V) {       // ragged last vocabulary tile: mask rows >= V
 #pragma unroll
@@ -204,7 +230,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(
         const float2* __restrict__ partials, const float* __restrict__ partial_sumz,
         int N, int D, int V, int S, int32_t ignore_index, float label_smoothing, float z_loss,
         float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status,
-        int v_off, float4* __restrict__ stats) {
+        int v_off, float4* __restrict__ stats, const Fp8Scales fp8) {
     const int l = threadIdx.x & 63;
     const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tok >= N) return;
@@ -235,6 +261,19 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     const uint16_t* h = H + (size_t)tok * D;
     const uint16_t* w = W + (size_t)(in_range ? y : 0) * D;
     float zy = 0.f;
+    if (fp8.hscale) {
+        // E4M3 rows: four codes per lane and step, decoded by the hardware conversion, the
+        // 128-block's two scale exponents applied exactly with ldexp
+        const uint8_t* h8 = (const uint8_t*)H + (size_t)tok * D;
+        const uint8_t* w8 = (const uint8_t*)W + (size_t)(in_range ? y : 0) * D;
+        for (int k = l * 4; in_range && k < D; k += 256) {
+            const int hv = *(const int*)(h8 + k), wv = *(const int*)(w8 + k);
+            const f32x2 h01 = __builtin_amdgcn_cvt_pk_f32_fp8(hv, false), h23 = __builtin_amdgcn_cvt_pk_f32_fp8(hv, true);
+            const f32x2 w01 = __builtin_amdgcn_cvt_pk_f32_fp8(wv, false), w23 = __builtin_amdgcn_cvt_pk_f32_fp8(wv, true);
+            const float p = fmaf(h01.x, w01.x, fmaf(h01.y, w01.y, fmaf(h23.x, w23.x, h23.y * w23.y)));
+            zy += ldexpf(p, scale_byte(fp8.hscale, fp8.hgroups, tok, k >> 7) + scale_byte(fp8.wscale, fp8.wgroups, y, k >> 7) - 254);
+        }
+    } else
     for (int k = l * 2; in_range && k < D; k += 128) {
         const uint32_t hv = *(const uint32_t*)(h + k), wv = *(const uint32_t*)(w + k);
         zy = fmaf(__uint_as_float(hv << 16), __uint_as_float(wv << 16), zy);
@@ -352,12 +391,13 @@ __global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict
 // contiguous) with full 512-byte rows.
 // Grid: one workgroup per tile of the [row block x chunk]; tile index -> (ti, vi).
 // ------------------------------------------------------------------------------------------
+template <bool FP8>
 __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
         const void* __restrict__ H, const void* __restrict__ W, const int32_t* __restrict__ labels,
         const float* __restrict__ lse, const float* __restrict__ dloss, const float* __restrict__ mean_scale,
         int N, int D, int V, int32_t ignore_index, float label_smoothing, float z_loss,
         int row0, int n_row_tiles, int v0, int n_v_tiles,
-        uint16_t* __restrict__ G, int ldg, int v_off, int V_total) {
+        uint16_t* __restrict__ G, int ldg, int v_off, int V_total, const Fp8Scales fp8) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -406,9 +446,18 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 
     OperandTile<true, Cfg::BM> Aop;
     OperandTile<true, Cfg::BN> Bop;
-    Aop.init(W, D, vt0, V, D);
-    Bop.init(H, D, tok0, N, D);
-    gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+    const int ld = FP8 ? D / 2 : D;               // row length in 2-byte units
+    Aop.init(W, ld, vt0, V, ld);
+    Bop.init(H, ld, tok0, N, ld);
+    if (FP8) {
+        ScaleGroup SA, SB;
+        const int b_row0 = tok0 + wave_n<Cfg>() * (Cfg::TN * 32);
+        SA.init(fp8.wscale, fp8.wgroups, (vt0 + wm * (Cfg::TM * 32)) >> 7);
+        SB.init(fp8.hscale, fp8.hgroups, b_row0 >> 7);
+        gemm_mainloop_fp8<Cfg>(acc, Aop, Bop, SA, SB, (b_row0 >> 6) & 1, D, smem);
+    } else {
+        gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
+    }
 
     CCE_LDS unsigned char* live_flags = (CCE_LDS unsigned char*)(smem + 256 * kGRowBytes);
     if (threadIdx.x < Cfg::BN) live_flags[threadIdx.x] = row_live ? 1 : 0;
@@ -842,9 +891,11 @@ static bool ensure_kernel_attributes() {
     if (!hip_ok(hipGetDevice(&dev))) return false;
     if (dev < 0 || dev >= 64) return false;
     if (done[dev]) return true;
-    if (!allow_big_lds(lse_partial_kernel<false>, TileBig::kLdsBytes)) return false;
-    if (!allow_big_lds(lse_partial_kernel<true>, TileBig::kLdsBytes)) return false;
-    if (!allow_big_lds(grad_tile_kernel, kGradTileLds)) return false;
+    if (!allow_big_lds(lse_partial_kernel<false, false>, TileBig::kLdsBytes)) return false;
+    if (!allow_big_lds(lse_partial_kernel<true, false>, TileBig::kLdsBytes)) return false;
+    if (!allow_big_lds(lse_partial_kernel<false, true>, TileBig::kLdsBytes)) return false;
+    if (!allow_big_lds(grad_tile_kernel<false>, kGradTileLds)) return false;
+    if (!allow_big_lds(grad_tile_kernel<true>, kGradTileLds)) return false;
     if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return false;
     if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return false;
     done[dev] = true;
@@ -894,9 +945,15 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
                         int64_t N, int64_t D, int64_t V, int32_t ignore_index,
                         float label_smoothing, float z_loss,
                         float* loss, float* lse, float* mean_loss,
-                        int64_t v_off, float* stats, bool want_sumz,
+                        int64_t v_off, float* stats, bool want_sumz, const Fp8Scales* fp8_in,
                         void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
+    Fp8Scales fp8 = {nullptr, nullptr, 0, 0};
+    if (fp8_in) {
+        fp8 = *fp8_in;
+        if (!fp8.hscale || !fp8.wscale || D % 128 != 0) return fp8.hscale && fp8.wscale ? CCE_ERR_UNSUPPORTED : CCE_ERR_INVALID;
+        if (((uintptr_t)fp8.hscale | (uintptr_t)fp8.wscale) & 3) return CCE_ERR_INVALID;
+    }
     if (!stats && (!loss || !lse)) return CCE_ERR_INVALID;
     if (((uintptr_t)loss | (uintptr_t)lse | (uintptr_t)mean_loss) & 3) return CCE_ERR_INVALID;
     if ((uintptr_t)stats & 15) return CCE_ERR_INVALID;
@@ -915,17 +972,20 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     {
         ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
-        if (smooth)
-            hipLaunchKernelGGL(lse_partial_kernel<true>, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz);
+        if (fp8_in)
+            hipLaunchKernelGGL((lse_partial_kernel<false, true>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
+        else if (smooth)
+            hipLaunchKernelGGL((lse_partial_kernel<true, false>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
         else
-            hipLaunchKernelGGL(lse_partial_kernel<false>, dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz);
+            hipLaunchKernelGGL((lse_partial_kernel<false, false>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
     }
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
                        (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials, (const float*)sumz,
                        (int)N, (int)D, (int)V, p.S, ignore_index, label_smoothing, z_loss, loss, lse, status,
-                       (int)v_off, (float4*)stats);
+                       (int)v_off, (float4*)stats, fp8);
     if (mean_loss && !stats)
         hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
                            (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss);
@@ -939,7 +999,7 @@ int cce_forward_ex(const void* hidden, const void* weight, const int32_t* labels
                    float* loss, float* lse, float* mean_loss,
                    void* workspace, size_t workspace_bytes, void* stream_) {
     return forward_impl(hidden, weight, labels, N, D, V, ignore_index, label_smoothing, z_loss,
-                        loss, lse, mean_loss, 0, nullptr, false, workspace, workspace_bytes, stream_);
+                        loss, lse, mean_loss, 0, nullptr, false, nullptr, workspace, workspace_bytes, stream_);
 }
 
 int cce_shard_forward(const void* hidden, const void* weight_shard, const int32_t* labels,
@@ -947,7 +1007,7 @@ int cce_shard_forward(const void* hidden, const void* weight_shard, const int32_
                       float* stats, void* workspace, size_t workspace_bytes, void* stream_) {
     if (!stats) return CCE_ERR_INVALID;
     return forward_impl(hidden, weight_shard, labels, N, D, Vs, -1, 0.f, 0.f, nullptr, nullptr, nullptr,
-                        vocab_offset, stats, want_sumz != 0, workspace, workspace_bytes, stream_);
+                        vocab_offset, stats, want_sumz != 0, nullptr, workspace, workspace_bytes, stream_);
 }
 
 int cce_shard_merge(const float* stats, int P, const int32_t* labels, int64_t N, int64_t V_total,
@@ -983,8 +1043,19 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
                          int64_t N, int64_t D, int64_t V, int64_t v_off, int64_t V_total, int32_t ignore_index,
                          float label_smoothing, float z_loss,
                          void* dHidden, float* dW, int accumulate_dW,
+                         const void* logit_hidden, const void* logit_weight, const Fp8Scales* fp8_in,
                          void* workspace, size_t workspace_bytes, void* stream_) {
     Plan p;
+    // The logit tiles are recomputed from logit_hidden / logit_weight (the bf16 operands, or
+    // their E4M3 copies with fp8_in); the two gradient contractions always use the bf16 ones.
+    Fp8Scales fp8 = {nullptr, nullptr, 0, 0};
+    if (fp8_in) {
+        fp8 = *fp8_in;
+        if (!fp8.hscale || !fp8.wscale || !logit_hidden || !logit_weight) return CCE_ERR_INVALID;
+        if (D % 128 != 0) return CCE_ERR_UNSUPPORTED;
+        if (((uintptr_t)fp8.hscale | (uintptr_t)fp8.wscale) & 3) return CCE_ERR_INVALID;
+        if (((uintptr_t)logit_hidden | (uintptr_t)logit_weight) & 15) return CCE_ERR_INVALID;
+    }
     if (!lse || !dHidden || !dW) return CCE_ERR_INVALID;
     if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
@@ -1027,10 +1098,16 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         // 1. gradient tiles of this [row block x chunk]
         {
             ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
-            hipLaunchKernelGGL(grad_tile_kernel, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
-                               hidden, weight, labels, lse, dloss, (const float*)mean_scale,
-                               (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
-                               (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total);
+            if (fp8_in)
+                hipLaunchKernelGGL(grad_tile_kernel<true>, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
+                                   logit_hidden, logit_weight, labels, lse, dloss, (const float*)mean_scale,
+                                   (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
+                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8);
+            else
+                hipLaunchKernelGGL(grad_tile_kernel<false>, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
+                                   hidden, weight, labels, lse, dloss, (const float*)mean_scale,
+                                   (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
+                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8);
         }
         // 2. both contractions in one launch
         // dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
@@ -1075,7 +1152,28 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
                     void* dHidden, float* dW, int accumulate_dW,
                     void* workspace, size_t workspace_bytes, void* stream_) {
     return backward_impl(hidden, weight, labels, lse, dloss, grad_scale, N, D, V, 0, V, ignore_index,
-                         label_smoothing, z_loss, dHidden, dW, accumulate_dW, workspace, workspace_bytes, stream_);
+                         label_smoothing, z_loss, dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr,
+                         workspace, workspace_bytes, stream_);
+}
+
+int cce_fp8_forward(const void* hidden_q, const void* hidden_scales, const void* weight_q, const void* weight_scales,
+                    const int32_t* labels, int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                    float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+    const Fp8Scales fp8 = {hidden_scales, weight_scales, (int)((N + 127) / 128), (int)((V + 127) / 128)};
+    return forward_impl(hidden_q, weight_q, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+                        0, nullptr, false, &fp8, workspace, workspace_bytes, stream_);
+}
+
+int cce_fp8_backward(const void* hidden_q, const void* hidden_scales, const void* weight_q, const void* weight_scales,
+                     const void* hidden, const void* weight, const int32_t* labels,
+                     const float* lse, const float* dloss,
+                     int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                     void* dHidden, float* dW, int accumulate_dW,
+                     void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!dloss) return CCE_ERR_INVALID;
+    const Fp8Scales fp8 = {hidden_scales, weight_scales, (int)((N + 127) / 128), (int)((V + 127) / 128)};
+    return backward_impl(hidden, weight, labels, lse, dloss, 1.f, N, D, V, 0, V, ignore_index, 0.f, 0.f,
+                         dHidden, dW, accumulate_dW, hidden_q, weight_q, &fp8, workspace, workspace_bytes, stream_);
 }
 
 int cce_shard_backward(const void* hidden, const void* weight_shard, const int32_t* labels,
@@ -1086,7 +1184,7 @@ int cce_shard_backward(const void* hidden, const void* weight_shard, const int32
                        void* workspace, size_t workspace_bytes, void* stream_) {
     return backward_impl(hidden, weight_shard, labels, lse, dloss, grad_scale, N, D, Vs, vocab_offset, V_total,
                          ignore_index, label_smoothing, z_loss, dHidden_partial, dW_shard, accumulate_dW,
-                         workspace, workspace_bytes, stream_);
+                         nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_);
 }
 
 int cce_backward(const void* hidden, const void* weight, const int32_t* labels,

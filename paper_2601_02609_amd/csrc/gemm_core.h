@@ -315,6 +315,140 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     barrier_pending_loads<0>();
 }
 
+// ------------------------------------------------------------------------------------------
+// FP8 (E4M3) variant of the main loop for two K-major operands with block scales: one
+// power-of-two scale (a biased exponent byte, as the block-scaled MFMA takes it) per row and
+// 128 consecutive K elements.  v_mfma_scale_f32_32x32x64_f8f6f4 multiplies 64 K values per
+// instruction and applies both operands' scales itself, at twice the bf16 rate for the same
+// LDS and global traffic per instruction: a 128-byte row of a stage now holds 128 K values,
+// so the stage geometry, the global->LDS loads and the swizzle are those of the bf16 loop
+// (the operands are handed in as bf16 matrices of half the width), and a K slice is 128.
+//
+// A lane's 32 operand bytes are the two 16-byte fragments the bf16 loop would read for two
+// consecutive k16 steps.  Which K positions the hardware assigns to them does not matter:
+// A and B use the same assignment, a dot product does not depend on the order of its terms,
+// and all 64 K values of an instruction lie in one 128-block, i.e. share one scale per row.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+// Block scales of a quantised matrix, in the order the block-scaled MFMA consumes them:
+// [D / 128 blocks][ceil(rows / 128) groups][32][4] bytes -- byte j of dword i of a group is the
+// exponent byte of row 128 g + 32 j + i.  A wavefront whose 32-row blocks start at a multiple
+// of 128 rows then gets the scales of four blocks with ONE dword load per lane and 128-block,
+// and picks block j with the instruction's byte selector.
+struct ScaleGroup {
+    const uint32_t* p;      // this lane's dword of K block 0
+    uint32_t step;          // dwords from one K block to the next
+    __device__ __forceinline__ void init(const void* scales, int groups, int group) {
+        group = group < groups ? group : groups - 1;            // rows past the matrix are masked by the caller
+        p = (const uint32_t*)scales + (size_t)group * 32 + (threadIdx.x & 31);
+        step = (uint32_t)groups * 32u;
+    }
+    __device__ __forceinline__ uint32_t load(int kb) const { return p[(size_t)kb * step]; }
+};
+
+// One block-scaled FP8 MFMA; OA / OB select the scale byte of each operand (compile time).
+template <int OA, int OB>
+__device__ __forceinline__ f32x16 mfma_fp8(const i32x8 a, const i32x8 b, const f32x16 c, int sa, int sb) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, OA, sa, OB, sb);
+}
+__device__ __forceinline__ f32x16 mfma_fp8_sel(int oa, int ob, const i32x8 a, const i32x8 b, const f32x16 c, int sa, int sb) {
+    switch (oa * 2 + ob) {          // folded after unrolling
+        case 0: return mfma_fp8<0, 0>(a, b, c, sa, sb);
+        case 1: return mfma_fp8<0, 1>(a, b, c, sa, sb);
+        case 2: return mfma_fp8<1, 0>(a, b, c, sa, sb);
+        case 3: return mfma_fp8<1, 1>(a, b, c, sa, sb);
+        case 4: return mfma_fp8<2, 0>(a, b, c, sa, sb);
+        case 5: return mfma_fp8<2, 1>(a, b, c, sa, sb);
+        case 6: return mfma_fp8<3, 0>(a, b, c, sa, sb);
+        default: return mfma_fp8<3, 1>(a, b, c, sa, sb);
+    }
+}
+
+// SA: scale group of the wavefront's TM = 4 A blocks (128 rows); SB: scale group that
+// contains its TN = 2 B blocks, b_half = which half of that group (0: rows 0..63).
+template <class Cfg>
+__device__ __forceinline__ void gemm_mainloop_fp8(f32x16 (&acc)[Cfg::TM][Cfg::TN],
+                                                   const OperandTile<true, Cfg::BM>& A,
+                                                   const OperandTile<true, Cfg::BN>& B,
+                                                   const ScaleGroup& SA, const ScaleGroup& SB, int b_half,
+                                                   int k_total, CCE_LDS char* smem) {
+    static_assert(Cfg::STAGES == 2 && Cfg::KG == 1 && Cfg::TM == 4 && Cfg::TN == 2, "256 x 256 tile, two stages");
+    FragAddr<true, Cfg::BM, Cfg::TM, 4, 1> fa;
+    FragAddr<true, Cfg::BN, Cfg::TN, 4, 1> fb;
+    fa.init(wave_m<Cfg>() * (Cfg::TM * 32), 0);
+    fb.init(wave_n<Cfg>() * (Cfg::TN * 32), 0);
+    auto frag = [](const CCE_LDS char* op, uint32_t a, int b) {
+        return *(const CCE_LDS i32x4*)(op + a + b * (32 * 128));
+    };
+
+    const int KT = (k_total + 127) / 128;
+    const int b_shift = 16 * b_half;
+    uint32_t sa_next = SA.load(0), sb_next = SB.load(0);
+
+    A.issue(smem, 0);
+    B.issue(smem + Cfg::kAStage, 0);
+    barrier_pending_loads<0>();
+
+    // A fragments are refreshed in place, block by block, behind the MFMAs that used them; B
+    // fragments (needed by every block of a step) are double buffered.
+    i32x4 af[Cfg::TM][2], bfr[2][Cfg::TN][2];
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm) { af[bm][0] = frag(smem, fa.a[0], bm); af[bm][1] = frag(smem, fa.a[1], bm); }
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        bfr[0][bn][0] = frag(smem + Cfg::kAStage, fb.a[0], bn);
+        bfr[0][bn][1] = frag(smem + Cfg::kAStage, fb.a[1], bn);
+    }
+
+    int cur_s = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        CCE_LDS char* cur = smem + cur_s * Cfg::kStage;
+        CCE_LDS char* nxt = smem + (cur_s ^ 1) * Cfg::kStage;
+        const bool more = kt + 1 < KT;
+        // scales of this slice (requested one slice ago, complete since the last barrier) and
+        // request of the next slice's, ahead of the operand loads
+        const int sa = (int)sa_next, sb = (int)(sb_next >> b_shift);
+        const int kn = more ? kt + 1 : kt;
+        sa_next = SA.load(kn);
+        sb_next = SB.load(kn);
+        if (more) {
+            A.issue(nxt, (kt + 1) * kBK);
+            B.issue(nxt + Cfg::kAStage, (kt + 1) * kBK);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int c = t, n = t ^ 1;
+            const CCE_LDS char* src = cur;
+            int j0 = 2;
+            if (t == 1) {
+                // slice kt + 1 must have landed before its fragments are read
+                barrier_pending_loads<0>();
+                src = nxt;
+                j0 = 0;
+            }
+#pragma unroll
+            for (int bn = 0; bn < Cfg::TN; ++bn) {
+                bfr[n][bn][0] = frag(src + Cfg::kAStage, fb.a[j0], bn);
+                bfr[n][bn][1] = frag(src + Cfg::kAStage, fb.a[j0 + 1], bn);
+            }
+#pragma unroll
+            for (int bm = 0; bm < Cfg::TM; ++bm) {
+                const i32x8 a8 = __builtin_shufflevector(af[bm][0], af[bm][1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int bn = 0; bn < Cfg::TN; ++bn) {
+                    const i32x8 b8 = __builtin_shufflevector(bfr[c][bn][0], bfr[c][bn][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc[bm][bn] = mfma_fp8_sel(bm, bn, a8, b8, acc[bm][bn], sa, sb);
+                }
+                af[bm][0] = frag(src, fa.a[j0], bm);
+                af[bm][1] = frag(src, fa.a[j0 + 1], bm);
+            }
+        }
+        cur_s ^= 1;
+    }
+    barrier_pending_loads<0>();
+}
+
 // Tile coordinates of accumulator element acc[bm][bn][r] of the calling lane.
 template <class Cfg>
 __device__ __forceinline__ int acc_row(int bm, int r) {

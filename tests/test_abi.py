@@ -25,7 +25,7 @@ def declared_symbols():
             continue
         text = open(os.path.join(inc, fn)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(cce_[a-z_]+)\s*\(", text))
+        names |= set(re.findall(r"\b(cce_[a-z0-9_]+)\s*\(", text))
     return sorted(names)
 
 
