@@ -409,6 +409,10 @@ __device__ __forceinline__ void gemm_mainloop_fp8(f32x16 (&acc)[Cfg::TM][Cfg::TN
         // scales of this slice (requested one slice ago, complete since the last barrier) and
         // request of the next slice's, ahead of the operand loads
         const int sa = (int)sa_next, sb = (int)(sb_next >> b_shift);
+        // Consume the two scale words HERE, before this iteration's operand loads are issued:
+        // the compiler places its wait for them at their first use and cannot see the
+        // inline-assembly loads, so a first use after those would make it wait for them too.
+        asm volatile("" :: "v"(sa), "v"(sb));
         const int kn = more ? kt + 1 : kt;
         sa_next = SA.load(kn);
         sb_next = SB.load(kn);
@@ -443,6 +447,14 @@ __device__ __forceinline__ void gemm_mainloop_fp8(f32x16 (&acc)[Cfg::TM][Cfg::TN
                 af[bm][0] = frag(src, fa.a[j0], bm);
                 af[bm][1] = frag(src, fa.a[j0 + 1], bm);
             }
+            // issue order for the scheduler: the four B reads behind the first two MFMAs, then
+            // each A block's two reads behind the MFMA that follows the last use of the block
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         cur_s ^= 1;
     }
