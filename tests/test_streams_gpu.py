@@ -68,3 +68,64 @@ def test_graph_capture_and_replay(B):
         for k in ("loss", "lse", "dH", "dW"):
             assert torch.equal(ref[k], b[k]), (rep, k)
         assert float(junk) == float(junk)
+
+
+def _fp8_step(B, b, stream=None):
+    B.cce_quantize_e4m3(b["H"], q=b["hq"], scales=b["hs"], stream=stream)
+    B.cce_quantize_e4m3(b["W"], q=b["wq"], scales=b["wsc"], stream=stream)
+    B.cce_fp8_forward(b["hq"], b["hs"], b["wq"], b["wsc"], b["y"], IGN, workspace=b["ws"], loss=b["loss"],
+                      lse=b["lse"], stream=stream)
+    B.cce_fp8_backward(b["hq"], b["hs"], b["wq"], b["wsc"], b["H"], b["W"], b["y"], b["lse"], b["dl"], IGN,
+                       workspace=b["ws"], d_hidden=b["dH"], d_weight=b["dW"], stream=stream)
+
+
+def _shard_step(B, b, stream=None):
+    V = b["W"].shape[0]
+    half = (V // 2) & ~7
+    for p, (lo, hi) in enumerate([(0, half), (half, V)]):
+        B.cce_shard_forward(b["H"], b["W"][lo:hi], b["y"], lo, stats=b["stats"][p], workspace=b["ws"], stream=stream)
+    # the merge allocates its outputs in the binding; copy them into the fixed buffers
+    loss, lse, _ = B.cce_shard_merge(b["stats"], b["y"], V, IGN, stream=stream)
+    b["loss"].copy_(loss)
+    b["lse"].copy_(lse)
+    lo, hi = half, V
+    B.cce_shard_backward(b["H"], b["W"][lo:hi], b["y"], b["lse"], b["dl"], lo, V, IGN, workspace=b["ws"],
+                         d_hidden=b["dH"], d_weight=b["dW"][lo:hi], stream=stream)
+
+
+@pytest.mark.parametrize("which", ["fp8", "shard"])
+def test_graph_capture_of_the_variants(B, which):
+    """The FP8 and the vocabulary-shard entry points are launches only as well: captured,
+    replayed three times with eager work in between, every replay equal to the eager result."""
+    w = I.make_workload(I.custom_spec(520, 256, 2100, seed=43, ignore_frac=0.1))
+    step = _fp8_step if which == "fp8" else _shard_step
+    def buffers():
+        b = _buffers(B, w)
+        N, D = w.hidden.shape
+        V = w.weight.shape[0]
+        b["hq"] = torch.empty(N, D, dtype=torch.uint8, device="cuda")
+        b["wq"] = torch.empty(V, D, dtype=torch.uint8, device="cuda")
+        b["hs"] = torch.empty(B.fp8_scale_bytes(N, D), dtype=torch.uint8, device="cuda")
+        b["wsc"] = torch.empty(B.fp8_scale_bytes(V, D), dtype=torch.uint8, device="cuda")
+        b["stats"] = torch.empty(2, N, 4, device="cuda")
+        b["dW"].zero_()
+        return b
+    ref, b = buffers(), buffers()
+    step(B, ref)
+    step(B, b)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            step(B, b, stream=s)
+    for rep in range(3):
+        for k in ("loss", "lse", "dH", "dW", "hq", "hs"):
+            b[k].zero_()
+        junk = torch.randn(1 << 20, device="cuda").sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in ("loss", "lse", "dH", "dW"):
+            assert torch.equal(ref[k], b[k]), (which, rep, k)
+        assert float(junk) == float(junk)
