@@ -167,6 +167,17 @@ int cce_set_backward_tiling(int row_tiles, int vocab_tiles);
  * automatic choice.  Host only; the two outputs are host ints. */
 int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int* vocab_tiles);
 
+/* Tuning / testing aid like cce_set_backward_tiling: force the output tile of the two gradient
+ * contractions to 256 x tile_cols, tile_cols = 128 or 256; 0 restores the automatic choice.
+ * Results agree across the two up to fp32 summation order.  Host state only; not thread safe. */
+int cce_set_backward_gemm_tile(int tile_cols);
+
+/* Rows x columns of the output tile the two gradient contractions use for this shape (256 x 256
+ * or 256 x 128; chosen with the tiling, by the same cost model: the narrow tile when a chunk's
+ * outputs would otherwise be too few tiles to fill the GPU, or when D is not a multiple of 256).
+ * Host only; the two outputs are host ints. */
+int cce_get_backward_gemm_tile(int64_t N, int64_t D, int64_t V, int* tile_rows, int* tile_cols);
+
 /*
  * Measurement aid (not part of the paper's method): per-kernel-family GPU time from HIP
  * events recorded on the caller's stream around every launch of the three MFMA kernel

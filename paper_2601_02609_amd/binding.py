@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
     "cce_forward_ex", "cce_backward_ex",
     "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
-    "cce_get_backward_tiling",
+    "cce_get_backward_tiling", "cce_get_backward_gemm_tile", "cce_set_backward_gemm_tile",
     # include/cce_aux.h
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
     "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
@@ -89,6 +89,10 @@ def lib() -> ctypes.CDLL:
     L.cce_set_backward_tiling.argtypes = [ctypes.c_int, ctypes.c_int]
     L.cce_get_backward_tiling.restype = ctypes.c_int
     L.cce_get_backward_tiling.argtypes = [i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
+    L.cce_set_backward_gemm_tile.restype = ctypes.c_int
+    L.cce_set_backward_gemm_tile.argtypes = [ctypes.c_int]
+    L.cce_get_backward_gemm_tile.restype = ctypes.c_int
+    L.cce_get_backward_gemm_tile.argtypes = [i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
     L.cce_rmsnorm_workspace_bytes.restype = sz
     L.cce_rmsnorm_workspace_bytes.argtypes = [i64, i64]
     L.cce_rmsnorm_forward.restype = ctypes.c_int
@@ -301,6 +305,22 @@ def get_backward_tiling(N: int, D: int, V: int) -> Tuple[int, int]:
     rc = lib().cce_get_backward_tiling(N, D, V, ctypes.byref(a), ctypes.byref(b))
     if rc != CCE_OK:
         raise CCEError(rc, "cce_get_backward_tiling")
+    return int(a.value), int(b.value)
+
+
+def set_backward_gemm_tile(tile_cols: int = 0) -> None:
+    """Force the contraction output tile to 256 x tile_cols (128 or 256); 0 = automatic."""
+    rc = lib().cce_set_backward_gemm_tile(tile_cols)
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_set_backward_gemm_tile")
+
+
+def get_backward_gemm_tile(N: int, D: int, V: int) -> Tuple[int, int]:
+    """(rows, columns) of the contraction output tile chosen for this shape."""
+    a, b = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().cce_get_backward_gemm_tile(N, D, V, ctypes.byref(a), ctypes.byref(b))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_get_backward_gemm_tile")
     return int(a.value), int(b.value)
 
 

@@ -727,6 +727,7 @@ static int device_cu_count() {
 struct Plan {
     int TT, VT, S;              // forward: token tiles, vocabulary tiles, vocabulary splits
     int64_t Nb, Vc;             // backward: rows per row block, vocabulary columns per chunk (multiples of 256)
+    int gemm_kind;              // backward: output tile of the contractions, 0 = 256 x 256, 1 = 256 x 128
     size_t off_status, off_partials, off_sumz, off_dhacc, off_g, total;
 };
 
@@ -734,18 +735,22 @@ struct Plan {
 // keeps the backward chunks large enough to fill the GPU.
 static constexpr size_t kBudgetFloor = 48u << 20;
 
-// Output tile of the two gradient contractions, by hidden size: 256 x 256 when D is a
-// multiple of 256, else 256 x 128 (D = 896 = 7 x 128).  (A 128 x 224 tile, which would give
-// D = 896 exactly 256 equal tiles per 4096 x 4096 chunk, was measured 3 % slower: its
-// 32 x 224 wavefront tiles need 1.14 LDS fragment reads per MFMA instead of 0.75.)
+// Output tiles of the two gradient contractions: 256 x 256, or 256 x 128 with two K groups.
+// The planner picks per shape: the narrow tile costs about 10 % more per flop (more operand
+// bytes per MFMA) but gives twice as many tiles, which matters when a chunk's outputs are too
+// few to fill the GPU (D = 1024: 124 big tiles per 4096 x 4096 chunk against 248 narrow ones)
+// or when D is not a multiple of 256 (D = 896 = 7 x 128).  (A 128 x 224 tile, which would give
+// D = 896 exactly 256 equal tiles per chunk, was measured 3 % slower: its 32 x 224 wavefront
+// tiles need 1.14 LDS fragment reads per MFMA instead of 0.75.)
 struct GemmTile { int kind, bm, bn; double us_per_slice; };
-static GemmTile gemm_tile_for(int64_t D) {
-    if (D % 256 == 0) return {0, TileBig::BM, TileBig::BN, 2.0};
+static GemmTile gemm_tile_of_kind(int kind) {
+    if (kind == 0) return {0, TileBig::BM, TileBig::BN, 2.0};
     return {1, TileNarrow::BM, TileNarrow::BN, 1.1};
 }
 
 // Backward tiling forced by cce_set_backward_tiling (0 = automatic).
 static int g_force_row_tiles = 0, g_force_vocab_tiles = 0;
+static int g_force_gemm_cols = 0;        // cce_set_backward_gemm_tile: 0 = automatic, 128 or 256
 
 // Rough time model of the backward pipeline, in microseconds, used only to rank tilings.
 // One compute unit runs one workgroup at a time.  Measured on MI355X with random bf16 data:
@@ -800,19 +805,29 @@ struct BackwardModel {
 
 static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     if (N <= 0 || D <= 0 || V <= 0) return false;
-    struct Key { int64_t N, D, V; int fa, fb; Plan plan; bool valid; };
-    static thread_local Key cache = {0, 0, 0, 0, 0, {}, false};
+    struct Key { int64_t N, D, V; int fa, fb, fc; Plan plan; bool valid; };
+    static thread_local Key cache = {0, 0, 0, 0, 0, 0, {}, false};
     if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.fa == g_force_row_tiles &&
-        cache.fb == g_force_vocab_tiles) { *p = cache.plan; return true; }
+        cache.fb == g_force_vocab_tiles && cache.fc == g_force_gemm_cols) { *p = cache.plan; return true; }
 
     const int cus = device_cu_count();
     const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
     p->TT = (int)(Np / 256);
     p->VT = (int)(Vp / 256);
-    int S = (cus + p->TT - 1) / p->TT;
-    if (S > p->VT) S = p->VT;
-    if (S < 1) S = 1;
-    p->S = S;
+    // Vocabulary splits of the forward: TT x S workgroups run in rounds of `cus`, each walking
+    // ceil(VT / S) vocabulary tiles; take the S with the fewest tile-times (the smallest on a tie).
+    {
+        int best_s = 1;
+        int64_t best_cost = INT64_MAX;
+        const int s_max = p->VT < 2 * cus ? p->VT : 2 * cus;
+        for (int s = 1; s <= s_max; ++s) {
+            const int64_t rounds = ((int64_t)p->TT * s + cus - 1) / cus;
+            const int64_t cost = rounds * ((p->VT + s - 1) / s);
+            if (cost < best_cost) { best_cost = cost; best_s = s; }
+        }
+        p->S = best_s;
+    }
+    const int S = p->S;
 
     // per (token, split): (max, sum-exp) pair + the logit sum that label smoothing needs
     const size_t md_bytes = (size_t)round_up((int64_t)N * S * 8, 256);
@@ -825,14 +840,17 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     auto bytes_needed = [&](int64_t a, int64_t b) {
         return (double)fixed + (double)round_up(a * 256 * D * 4, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
     };
-    BackwardModel model{cus, D, gemm_tile_for(D)};
-    int best_a = 1, best_b = 1;
-    if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
-        best_a = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
-        best_b = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
-    } else {
+    // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
+    auto plan_for_kind = [&](int kind, int* a_out, int* b_out) {
+        BackwardModel model{cus, D, gemm_tile_of_kind(kind)};
+        if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
+            *a_out = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
+            *b_out = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
+            return;
+        }
         double best_cost = 1e300;
         const int a_max = p->TT < 64 ? p->TT : 64, b_max = p->VT < 128 ? p->VT : 128;
+        *a_out = 1; *b_out = 1;
         for (int a = 1; a <= a_max; ++a) {
             for (int b = 1; b <= b_max; ++b) {
                 if (bytes_needed(a, b) > (double)budget && !(a == 1 && b == 1)) break;
@@ -844,10 +862,27 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
                 };
                 const double cost = (nblk == 1) ? block_cost(a_last, false)
                                                 : block_cost(a, false) + (nblk - 2) * block_cost(a, true) + block_cost(a_last, true);
-                if (cost < best_cost) { best_cost = cost; best_a = a; best_b = b; }
+                if (cost < best_cost) { best_cost = cost; *a_out = a; *b_out = b; }
             }
         }
+    };
+    // 256 x 256 tiles when D is a multiple of 256 and they fill the rounds of `cus` workgroups
+    // of a contraction launch to at least 70 %; else 256 x 128.  (The cost model ranks tilings
+    // of one tile shape well but is off by ~15 % between the shapes, so the shape is decided
+    // by occupancy: measured, D = 1024 and 2048 gain 17 % with the narrow tile, D = 1536 with
+    // 77 % occupancy loses 6 %.)
+    int best_a = 1, best_b = 1, best_kind = 1;
+    if (g_force_gemm_cols != 0) {
+        best_kind = g_force_gemm_cols == 256 ? 0 : 1;
+        if (best_kind == 0) plan_for_kind(0, &best_a, &best_b);
+    } else if (D % 256 == 0) {
+        plan_for_kind(0, &best_a, &best_b);
+        const int64_t tiles = (int64_t)(best_a + best_b) * (D / 256);
+        const int64_t rounds = (tiles + cus - 1) / cus;
+        best_kind = (double)tiles >= 0.7 * (double)(rounds * cus) ? 0 : 1;
     }
+    if (best_kind == 1) plan_for_kind(1, &best_a, &best_b);
+    p->gemm_kind = best_kind;
     p->Nb = (int64_t)best_a * 256;
     p->Vc = (int64_t)best_b * 256;
     // the gradient chunk is addressed with 32-bit byte offsets (only a forced tiling can get here)
@@ -858,7 +893,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->off_dhacc = p->off_partials + partial_bytes;
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 4, 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
-    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, *p, true};
+    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, *p, true};
     return true;
 }
 
@@ -1074,7 +1109,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
                            labels, (int)N, (int)V_total, ignore_index, grad_scale, mean_scale);
     const int grad_lds = kGradTileLds;
 
-    const GemmTile gt = gemm_tile_for(D);
+    const GemmTile gt = gemm_tile_of_kind(p.gemm_kind);
     const int d_tiles = (int)((D + gt.bn - 1) / gt.bn);
     const int per256 = 256 / gt.bm;                               // contraction row tiles per 256 rows
 
@@ -1212,6 +1247,24 @@ int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int
     if (!make_plan(N, D, V, &p)) return CCE_ERR_INVALID;
     *row_tiles = (int)(p.Nb / 256);
     *vocab_tiles = (int)(p.Vc / 256);
+    return CCE_OK;
+}
+
+int cce_set_backward_gemm_tile(int tile_cols) {
+    if (tile_cols != 0 && tile_cols != 128 && tile_cols != 256) return CCE_ERR_INVALID;
+    g_force_gemm_cols = tile_cols;
+    return CCE_OK;
+}
+
+int cce_get_backward_gemm_tile(int64_t N, int64_t D, int64_t V, int* tile_rows, int* tile_cols) {
+    Plan p;
+    if (!tile_rows || !tile_cols) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || V <= 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (!make_plan(N, D, V, &p)) return CCE_ERR_INVALID;
+    const GemmTile gt = gemm_tile_of_kind(p.gemm_kind);
+    *tile_rows = gt.bm;
+    *tile_cols = gt.bn;
     return CCE_OK;
 }
 

@@ -76,3 +76,19 @@ def test_forced_tiling_is_bounded(L):
     assert binding.get_backward_tiling(8192, 896, 151936) == (16, 16)
     with pytest.raises(binding.CCEError):
         binding.set_backward_tiling(3, 0)
+
+
+def test_contraction_tile_choice(L):
+    """256 x 128 tiles when D is not a multiple of 256 or when 256 x 256 tiles would fill less than
+    70 % of the workgroup rounds of a launch; the override wins over both."""
+    assert binding.get_backward_gemm_tile(8192, 896, 151936) == (256, 128)
+    assert binding.get_backward_gemm_tile(32768, 3584, 151936) == (256, 256)
+    assert binding.get_backward_gemm_tile(16384, 2048, 128256) == (256, 256)
+    assert binding.get_backward_gemm_tile(16384, 1024, 50257) == (256, 128)
+    try:
+        binding.set_backward_gemm_tile(256)
+        assert binding.get_backward_gemm_tile(8192, 896, 151936) == (256, 256)
+        binding.set_backward_gemm_tile(128)
+        assert binding.get_backward_gemm_tile(32768, 3584, 151936) == (256, 128)
+    finally:
+        binding.set_backward_gemm_tile(0)

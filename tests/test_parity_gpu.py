@@ -101,6 +101,23 @@ def test_backward_is_invariant_to_the_chunking(B, tiling):
     assert rel_fro(got[2], base[2]) <= 5e-3 and rel_fro(got[3], base[3]) <= 1e-5
 
 
+@pytest.mark.parametrize("shape", [(600, 512, 2100), (520, 896, 1300), (300, 1024, 700)])
+@pytest.mark.parametrize("cols", [128, 256])
+def test_backward_with_either_contraction_tile(B, shape, cols):
+    """The two gradient contractions run on 256 x 256 or 256 x 128 output tiles (picked per shape by
+    occupancy); both must meet the oracle for any D, multiple of 256 or not."""
+    N, D, V = shape
+    w = I.make_workload(I.custom_spec(N, D, V, seed=14, ignore_frac=0.2))
+    try:
+        B.set_backward_gemm_tile(cols)
+        assert B.get_backward_gemm_tile(N, D, V) == (256, cols)
+        check_against_oracle(B, w, w.dloss_var, f"tile256x{cols}")
+    finally:
+        B.set_backward_gemm_tile(0)
+    with pytest.raises(B.CCEError):
+        B.set_backward_gemm_tile(64)
+
+
 def test_single_token_single_class(B):
     w = I.make_workload(I.custom_spec(1, 64, 1, seed=2, ignore_frac=0.0, labels="uniform"))
     loss, lse, dH, dW = run_both(B, w, w.dloss_mean)
