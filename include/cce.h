@@ -38,9 +38,10 @@
  *     aborts across this boundary.  On an error return nothing was enqueued.
  *   - `workspace` is caller-owned device scratch of at least
  *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
- *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, an fp32 dHidden
- *     accumulator for one row block and one bf16 [row block x vocab chunk]
- *     gradient chunk; it never scales with N*V.  Contents are scratch: nothing
+ *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, the lower
+ *     halves of the fp32 dHidden sums of one row block (their upper halves live in
+ *     dHidden itself until the last vocabulary chunk rounds the sums to bf16 there) and
+ *     one bf16 [row block x vocab chunk] gradient chunk; it never scales with N*V.  Contents are scratch: nothing
  *     needs to survive between forward and backward except what the caller
  *     passes explicitly (lse).
  */
@@ -106,7 +107,8 @@ int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
  *   dloss    in  fp32 [N]     device   upstream gradient of each per-token loss
  *                                      (1/N_valid everywhere for a mean loss); entries
  *                                      at ignored rows are never used (may be NaN)
- *   dHidden  out bf16 [N, D]  device   fp32 accumulation, rounded to nearest even
+ *   dHidden  out bf16 [N, D]  device   fp32 accumulation, rounded to nearest even (used as
+ *                                      scratch for partial sums while the call runs)
  *   dW       out fp32 [V, D]  device   accumulate_dW == 0: overwritten;
  *                                      accumulate_dW != 0: the gradient is added to it
  * The logit gradient tile is rounded to bf16 (nearest even) before the two

@@ -520,8 +520,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 //   dH job (A K-major): C[token, d] = sum_v G[token, v] * W[v, d]
 //   dW job (A K-slow ): C[vocab, d] = sum_i G[i, vocab] * H[i, d]
 // A is the scratch chunk G (zero padded to tile multiples in both directions), B is a slice
-// of an input tensor in K-slow layout.  out_f32 (+)= C when `beta`; when out_bf16 is given
-// the sum is rounded to bf16 there instead.  Rows >= m_valid and columns >= n_valid are
+// of an input tensor in K-slow layout.  The result is added to / stored in the job's output
+// (see GemmJob for its two forms).  Rows >= m_valid and columns >= n_valid are
 // dropped.  Workgroups [0, first.n_work) serve the first job, the rest the second; the host
 // puts the job with the longer reduction first so that its tiles are dispatched first.
 // ------------------------------------------------------------------------------------------
@@ -534,13 +534,21 @@ constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
 constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, TileBig::BN);
 constexpr int kGemmLdsNarrow = gemm_lds_bytes(TileNarrow::kLdsBytes, TileNarrow::BM, TileNarrow::BN);
 
+// Output of a job, one of two forms:
+//   fp32 (the dW job): out_f32 (+)= C when `beta`.
+//   split (the dH job, out_f32 == nullptr): the fp32 running sum over the vocabulary chunks is
+//   kept as two 16-bit planes -- the upper halves of the fp32 words in the bf16 output tensor
+//   itself (out_hi, the caller's dHidden, whose final content is written by the last chunk), the
+//   lower halves in the workspace (out_lo) -- so that the accumulator costs 2 instead of 4
+//   workspace bytes per element; the split is exact.  `beta`: add to the stored sum; `final`:
+//   round the sum to bf16 into out_hi instead of storing the two planes.
 struct GemmJob {
     int a_kmajor;               // 1: A is K-major (the dH job), 0: A is K-slow (the dW job)
     const uint16_t* A; int lda; int a_free_n; int a_k_n;
     const void* B; int ldb; int b_k_n; int k_total;
     int n_tiles; int n_work; int m_valid; int n_valid;
     float* out_f32; int64_t ld_out; int beta;
-    uint16_t* out_bf16; int64_t ld_out_bf16;
+    uint16_t* out_hi; uint16_t* out_lo; int final;
 };
 
 template <class Cfg, bool A_KMAJOR>
@@ -585,14 +593,31 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     // as early as possible -- all chunks of a pass at once, right after the main loop /
     // the previous pass -- so that their latency hides under the staging through LDS
     // (whose barriers wait for LDS traffic only).
+    // (split form: words 0-1 of old[] hold the upper-half plane, words 2-3 the lower-half plane)
+    const bool split = j.out_f32 == nullptr;
     f32x4 old[kIters];
     auto fetch_old = [&](int pr0) {
 #pragma unroll
         for (int it = 0; it < kIters; ++it) {
             const int row = mi * Cfg::BM + pr0 + it * kRowsPerIter + my_row;
             old[it] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (j.beta && col_ok && row < j.m_valid) old[it] = *(const f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col);
+            if (j.beta && col_ok && row < j.m_valid) {
+                if (split) {
+                    const u32x2 hi = *(const u32x2*)(j.out_hi + (size_t)row * j.ld_out + col);
+                    const u32x2 lo = *(const u32x2*)(j.out_lo + (size_t)row * j.ld_out + col);
+                    old[it] = __builtin_bit_cast(f32x4, u32x4{hi.x, hi.y, lo.x, lo.y});
+                } else {
+                    old[it] = *(const f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col);
+                }
+            }
         }
+    };
+    // the four fp32 values of a chunk from its two planes
+    auto join_planes = [](const f32x4 planes) {
+        const u32x4 w = __builtin_bit_cast(u32x4, planes);
+        const u32x4 bits = {(w.x << 16) | (w.z & 0xffffu), (w.x & 0xffff0000u) | (w.z >> 16),
+                            (w.y << 16) | (w.w & 0xffffu), (w.y & 0xffff0000u) | (w.w >> 16)};
+        return __builtin_bit_cast(f32x4, bits);
     };
     fetch_old(0);
 
@@ -639,18 +664,25 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
         f32x4 v[kIters];
 #pragma unroll
         for (int it = 0; it < kIters; ++it)
-            v[it] = *(const CCE_LDS f32x4*)(smem + (it * kRowsPerIter + my_row) * kRowBytes + my_chunk * 16) + old[it];
+            v[it] = *(const CCE_LDS f32x4*)(smem + (it * kRowsPerIter + my_row) * kRowBytes + my_chunk * 16) +
+                    (split ? join_planes(old[it]) : old[it]);
 #pragma unroll
         for (int it = 0; it < kIters; ++it) {
             const int row = mi * Cfg::BM + pr0 + it * kRowsPerIter + my_row;
             if (!col_ok || row >= j.m_valid) continue;
-            if (j.out_bf16) {
+            if (!split) {
+                *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
+            } else if (j.final) {
                 union { __bf16 h[4]; u32x2 u; } cv;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[it][e];
-                *(u32x2*)(j.out_bf16 + (size_t)row * j.ld_out_bf16 + col) = cv.u;
+                *(u32x2*)(j.out_hi + (size_t)row * j.ld_out + col) = cv.u;
             } else {
-                *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
+                const u32x4 b = __builtin_bit_cast(u32x4, v[it]);
+                const u32x2 hi = {(b.y & 0xffff0000u) | (b.x >> 16), (b.w & 0xffff0000u) | (b.z >> 16)};
+                const u32x2 lo = {(b.y << 16) | (b.x & 0xffffu), (b.w << 16) | (b.z & 0xffffu)};
+                *(u32x2*)(j.out_hi + (size_t)row * j.ld_out + col) = hi;
+                *(u32x2*)(j.out_lo + (size_t)row * j.ld_out + col) = lo;
             }
         }
         if (pass + 1 < kPasses) {
@@ -838,7 +870,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
 
     // Row block of a tiles, vocabulary chunk of b tiles.
     auto bytes_needed = [&](int64_t a, int64_t b) {
-        return (double)fixed + (double)round_up(a * 256 * D * 4, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
+        return (double)fixed + (double)round_up(a * 256 * D * 2, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
     };
     // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
     auto plan_for_kind = [&](int kind, int* a_out, int* b_out) {
@@ -891,7 +923,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->off_partials = 256;
     p->off_sumz = p->off_partials + md_bytes;
     p->off_dhacc = p->off_partials + partial_bytes;
-    p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 4, 256);
+    p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 2, 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
     cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, *p, true};
     return true;
@@ -1100,7 +1132,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
-    float* dhacc = (float*)(ws + p.off_dhacc);
+    uint16_t* dh_lo = (uint16_t*)(ws + p.off_dhacc);     // lower halves of the fp32 dH sums (see GemmJob)
     uint16_t* G = (uint16_t*)(ws + p.off_g);
     // mean reduction: the common upstream gradient grad_scale / n_valid lives in the status block
     float* mean_scale = (float*)(ws + p.off_status + 64);
@@ -1152,8 +1184,8 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dh.B = (const void*)((const uint16_t*)weight + (size_t)st.v0 * D); dh.ldb = (int)D; dh.b_k_n = (int)st.cols;
         dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = st.row_tiles * per256 * d_tiles;
         dh.m_valid = (int)st.rows; dh.n_valid = (int)D;
-        dh.out_f32 = dhacc; dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
-        dh.out_bf16 = st.last_chunk ? (uint16_t*)dHidden + (size_t)st.r0 * D : (uint16_t*)nullptr; dh.ld_out_bf16 = D;
+        dh.out_f32 = nullptr; dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
+        dh.out_hi = (uint16_t*)dHidden + (size_t)st.r0 * D; dh.out_lo = dh_lo; dh.final = st.last_chunk ? 1 : 0;
         // dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
         GemmJob dw;
         dw.a_kmajor = 0;
@@ -1162,7 +1194,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dw.k_total = st.row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = st.v_tiles * per256 * d_tiles;
         dw.m_valid = (int)st.cols; dw.n_valid = (int)D;
         dw.out_f32 = dW + (size_t)st.v0 * D; dw.ld_out = D; dw.beta = (st.r0 > 0 || accumulate_dW) ? 1 : 0;
-        dw.out_bf16 = nullptr; dw.ld_out_bf16 = 0;
+        dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0;
         const bool dh_first = dh.k_total >= dw.k_total;          // longer reduction first
         const GemmJob& first = dh_first ? dh : dw;
         const GemmJob& second = dh_first ? dw : dh;
