@@ -57,6 +57,30 @@ int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, co
                          int64_t N, int64_t D, void* dx, float* dgamma, int accumulate_dgamma,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * RMSNorm with the residual add that precedes it fused in (fused RMSNorm-with-residual kernel):
+ *   h_ij = x_ij + residual_ij   computed in fp32, rounded once to bf16 and stored back into
+ *                               `residual` (the residual stream handed to whatever follows)
+ *   y, rstd                     cce_rmsnorm_forward of that stored h
+ *   x         in  bf16 [N, D]   the last block's output
+ *   residual  i/o bf16 [N, D]   in: the residual stream; out: h.  May not overlap x or y.
+ * One pass: 2 reads and 2 writes of N x D bf16 instead of the 3 + 2 of an add followed by a norm.
+ */
+int cce_rmsnorm_residual_forward(const void* x, void* residual, const void* gamma, int64_t N, int64_t D,
+                                 float eps, void* y, float* rstd, void* stream);
+
+/*
+ * Backward of the fused form.  h is what the forward left in `residual`; x and residual both
+ * receive the gradient of h:
+ *   dh = [cce_rmsnorm_backward of (h, gamma, rstd, dy)] + d_residual
+ *   d_residual  in  bf16 [N, D]  gradient arriving through the residual stream from whatever
+ *                                consumed h besides the norm; NULL = none (the final norm)
+ * The sum is formed in fp32 and rounded once.  Everything else as cce_rmsnorm_backward.
+ */
+int cce_rmsnorm_residual_backward(const void* h, const void* gamma, const float* rstd, const void* dy,
+                                  const void* d_residual, int64_t N, int64_t D, void* dh, float* dgamma,
+                                  int accumulate_dgamma, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of device workspace cce_grad_sumsq needs (a fixed number of partial sums). Host only. */
 size_t cce_sumsq_workspace_bytes(void);
 

@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = [
     "cce_get_backward_tiling", "cce_get_backward_gemm_tile", "cce_set_backward_gemm_tile",
     # include/cce_aux.h
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
+    "cce_rmsnorm_residual_forward", "cce_rmsnorm_residual_backward",
     "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
     "cce_mfma_probe", "cce_device_info",
     # include/cce_shard.h
@@ -99,6 +100,10 @@ def lib() -> ctypes.CDLL:
     L.cce_rmsnorm_forward.argtypes = [vp, vp, i64, i64, f32, vp, vp, vp]
     L.cce_rmsnorm_backward.restype = ctypes.c_int
     L.cce_rmsnorm_backward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_rmsnorm_residual_forward.restype = ctypes.c_int
+    L.cce_rmsnorm_residual_forward.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp]
+    L.cce_rmsnorm_residual_backward.restype = ctypes.c_int
+    L.cce_rmsnorm_residual_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_sumsq_workspace_bytes.restype = sz
     L.cce_sumsq_workspace_bytes.argtypes = []
     L.cce_grad_sumsq.restype = ctypes.c_int
@@ -392,6 +397,59 @@ def cce_rmsnorm_backward(x: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tenso
                                    dx.data_ptr(), dgamma.data_ptr(), 1 if accumulate_dgamma else 0,
                                    ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "cce_rmsnorm_backward")
     return dx, dgamma
+
+
+def cce_rmsnorm_residual_forward(x: torch.Tensor, residual: torch.Tensor, gamma: torch.Tensor, eps: float, *,
+                                 y: Optional[torch.Tensor] = None, rstd: Optional[torch.Tensor] = None,
+                                 stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """residual <- x + residual (in place), then (y, rstd) of the norm of that sum."""
+    N, D = x.shape
+    _check(x, torch.bfloat16, (N, D), "x")
+    _check(residual, torch.bfloat16, (N, D), "residual")
+    _check(gamma, torch.bfloat16, (D,), "gamma")
+    if y is None:
+        y = torch.empty_like(x)
+    if rstd is None:
+        rstd = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(y, torch.bfloat16, (N, D), "y")
+    _check(rstd, torch.float32, (N,), "rstd")
+    _rc(lib().cce_rmsnorm_residual_forward(x.data_ptr(), residual.data_ptr(), gamma.data_ptr(), N, D, eps,
+                                           y.data_ptr(), rstd.data_ptr(), _stream_ptr(stream)),
+        "cce_rmsnorm_residual_forward")
+    return y, rstd
+
+
+def cce_rmsnorm_residual_backward(h: torch.Tensor, gamma: torch.Tensor, rstd: torch.Tensor, dy: torch.Tensor,
+                                  d_residual: Optional[torch.Tensor] = None, *,
+                                  dh: Optional[torch.Tensor] = None, dgamma: Optional[torch.Tensor] = None,
+                                  accumulate_dgamma: bool = False, workspace: Optional[torch.Tensor] = None,
+                                  stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(dh bf16 [N, D], dgamma fp32 [D]): gradient of h = x + residual, d_residual added if given."""
+    N, D = h.shape
+    _check(h, torch.bfloat16, (N, D), "h")
+    _check(gamma, torch.bfloat16, (D,), "gamma")
+    _check(rstd, torch.float32, (N,), "rstd")
+    _check(dy, torch.bfloat16, (N, D), "dy")
+    if d_residual is not None:
+        _check(d_residual, torch.bfloat16, (N, D), "d_residual")
+    n = int(lib().cce_rmsnorm_workspace_bytes(N, D))
+    if n == 0:
+        raise CCEError(CCE_ERR_UNSUPPORTED, "cce_rmsnorm_workspace_bytes")
+    ws = workspace if workspace is not None else torch.empty(n, dtype=torch.uint8, device=h.device)
+    if dh is None:
+        dh = torch.empty_like(h)
+    _check(dh, torch.bfloat16, (N, D), "dh")
+    if dgamma is None:
+        if accumulate_dgamma:
+            raise ValueError("accumulate_dgamma needs an existing dgamma")
+        dgamma = torch.empty(D, dtype=torch.float32, device=h.device)
+    _check(dgamma, torch.float32, (D,), "dgamma")
+    _rc(lib().cce_rmsnorm_residual_backward(h.data_ptr(), gamma.data_ptr(), rstd.data_ptr(), dy.data_ptr(),
+                                            d_residual.data_ptr() if d_residual is not None else None, N, D,
+                                            dh.data_ptr(), dgamma.data_ptr(), 1 if accumulate_dgamma else 0,
+                                            ws.data_ptr(), ws.numel(), _stream_ptr(stream)),
+        "cce_rmsnorm_residual_backward")
+    return dh, dgamma
 
 
 def cce_grad_sumsq(grad: torch.Tensor, sumsq: Optional[torch.Tensor] = None, accumulate: bool = False, *,

@@ -56,12 +56,13 @@ __device__ __forceinline__ float wave_sum(float x) {
 template <int CH>      // 16-byte chunks a lane holds per row: D <= CH * 512
 __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
         const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, int N, int D, float eps,
-        uint16_t* __restrict__ y, float* __restrict__ rstd_out) {
+        uint16_t* __restrict__ y, float* __restrict__ rstd_out, uint16_t* residual) {
     const int l = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= N) return;
     const int chunks = D >> 3;
     const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
+    au32x4* rr = (au32x4*)(residual + (size_t)row * D);
     au32x4 xv[CH];
     float ss = 0.f;
 #pragma unroll
@@ -71,6 +72,18 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
             xv[i] = xr[c];
             float f[8];
             unpack8(xv[i], f);
+            if (residual) {
+                // fused residual add (fused RMSNorm-with-residual kernel): h = x + residual in
+                // fp32, rounded once to bf16, stored back as the new residual stream, and it is
+                // this stored value that is normalised
+                float r[8];
+                unpack8(rr[c], r);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] += r[e];
+                xv[i] = pack8(f);
+                rr[c] = xv[i];
+                unpack8(xv[i], f);
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
         }
@@ -104,7 +117,8 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
 template <int CH>
 __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
         const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, const float* __restrict__ rstd_in,
-        const uint16_t* __restrict__ dy, int N, int D, uint16_t* __restrict__ dx, float* __restrict__ partials) {
+        const uint16_t* __restrict__ dy, int N, int D, uint16_t* __restrict__ dx, float* __restrict__ partials,
+        const uint16_t* __restrict__ dres) {
     __shared__ float red[4][64 * 8];
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int chunks = D >> 3;
@@ -157,6 +171,12 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
                 unpack8(gr[c], ga);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = rstd * (ga[e] * gf[e] - xf[e] * rstd * cmean);
+                if (dres) {         // gradient arriving through the residual stream, added in fp32
+                    float u[8];
+                    unpack8(((const au32x4*)(dres + (size_t)row * D))[c], u);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += u[e];
+                }
                 dxr[c] = pack8(o);
             }
         }
@@ -209,6 +229,12 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
                 unpack8(gr[c], ga);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = rstd * (ga[e] * gf[e] - xf[e] * rstd * cmean);
+                if (dres) {
+                    float u[8];
+                    unpack8(((const au32x4*)(dres + (size_t)row * D))[c], u);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += u[e];
+                }
                 dxr[c] = pack8(o);
             }
         }
@@ -472,8 +498,8 @@ size_t cce_rmsnorm_workspace_bytes(int64_t N, int64_t D) {
     return (size_t)round_up((int64_t)norm_backward_blocks(N) * D * 4, 256);
 }
 
-int cce_rmsnorm_forward(const void* x, const void* gamma, int64_t N, int64_t D, float eps,
-                        void* y, float* rstd, void* stream_) {
+static int rmsnorm_forward_impl(const void* x, void* residual, const void* gamma, int64_t N, int64_t D, float eps,
+                                void* y, float* rstd, void* stream_) {
     if (!x || !gamma || !y || !rstd) return CCE_ERR_INVALID;
     if (N <= 0 || D <= 0 || !(eps >= 0.f)) return CCE_ERR_INVALID;
     if (!norm_shape_ok(N, D)) return CCE_ERR_UNSUPPORTED;
@@ -482,16 +508,27 @@ int cce_rmsnorm_forward(const void* x, const void* gamma, int64_t N, int64_t D, 
     const dim3 grid((unsigned)((N + 3) / 4));
     hipStream_t stream = (hipStream_t)stream_;
 #define CCE_NORM_FWD(CH) hipLaunchKernelGGL(rmsnorm_forward_kernel<CH>, grid, dim3(256), 0, stream, \
-        (const uint16_t*)x, (const uint16_t*)gamma, (int)N, (int)D, eps, (uint16_t*)y, rstd)
+        (const uint16_t*)x, (const uint16_t*)gamma, (int)N, (int)D, eps, (uint16_t*)y, rstd, (uint16_t*)residual)
     if (D <= 1024) CCE_NORM_FWD(2); else if (D <= 2048) CCE_NORM_FWD(4); else if (D <= 4096) CCE_NORM_FWD(8); else CCE_NORM_FWD(16);
 #undef CCE_NORM_FWD
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
 
-int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dy,
-                         int64_t N, int64_t D, void* dx, float* dgamma, int accumulate_dgamma,
-                         void* workspace, size_t workspace_bytes, void* stream_) {
+int cce_rmsnorm_forward(const void* x, const void* gamma, int64_t N, int64_t D, float eps,
+                        void* y, float* rstd, void* stream_) {
+    return rmsnorm_forward_impl(x, nullptr, gamma, N, D, eps, y, rstd, stream_);
+}
+
+int cce_rmsnorm_residual_forward(const void* x, void* residual, const void* gamma, int64_t N, int64_t D, float eps,
+                                 void* y, float* rstd, void* stream_) {
+    if (!residual || ((uintptr_t)residual & 15)) return CCE_ERR_INVALID;
+    return rmsnorm_forward_impl(x, residual, gamma, N, D, eps, y, rstd, stream_);
+}
+
+static int rmsnorm_backward_impl(const void* x, const void* gamma, const float* rstd, const void* dy, const void* dres,
+                                 int64_t N, int64_t D, void* dx, float* dgamma, int accumulate_dgamma,
+                                 void* workspace, size_t workspace_bytes, void* stream_) {
     if (!x || !gamma || !rstd || !dy || !dx || !dgamma || !workspace) return CCE_ERR_INVALID;
     if (N <= 0 || D <= 0) return CCE_ERR_INVALID;
     if (!norm_shape_ok(N, D)) return CCE_ERR_UNSUPPORTED;
@@ -502,13 +539,29 @@ int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, co
     const int blocks = norm_backward_blocks(N);
     float* partials = (float*)workspace;
 #define CCE_NORM_BWD(CH) hipLaunchKernelGGL(rmsnorm_backward_kernel<CH>, dim3(blocks), dim3(256), 0, stream, \
-        (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D, (uint16_t*)dx, partials)
+        (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D, (uint16_t*)dx, partials, \
+        (const uint16_t*)dres)
     if (D <= 1024) CCE_NORM_BWD(2); else if (D <= 2048) CCE_NORM_BWD(4); else if (D <= 4096) CCE_NORM_BWD(8); else CCE_NORM_BWD(16);
 #undef CCE_NORM_BWD
     hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 63) / 64)), dim3(256), 0, stream,
                        (const float*)partials, blocks, (int)D, dgamma, accumulate_dgamma ? 1 : 0);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
+}
+
+int cce_rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dy,
+                         int64_t N, int64_t D, void* dx, float* dgamma, int accumulate_dgamma,
+                         void* workspace, size_t workspace_bytes, void* stream_) {
+    return rmsnorm_backward_impl(x, gamma, rstd, dy, nullptr, N, D, dx, dgamma, accumulate_dgamma,
+                                 workspace, workspace_bytes, stream_);
+}
+
+int cce_rmsnorm_residual_backward(const void* h, const void* gamma, const float* rstd, const void* dy,
+                                  const void* d_residual, int64_t N, int64_t D, void* dh, float* dgamma,
+                                  int accumulate_dgamma, void* workspace, size_t workspace_bytes, void* stream_) {
+    if ((uintptr_t)d_residual & 15) return CCE_ERR_INVALID;
+    return rmsnorm_backward_impl(h, gamma, rstd, dy, d_residual, N, D, dh, dgamma, accumulate_dgamma,
+                                 workspace, workspace_bytes, stream_);
 }
 
 size_t cce_sumsq_workspace_bytes(void) { return (size_t)kSumsqBlocks * sizeof(double); }

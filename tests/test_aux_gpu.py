@@ -52,6 +52,39 @@ def test_rmsnorm_matches_oracle(B, shape):
     assert np.abs(dgamma.cpu().numpy() - o_dgamma).max() <= 1e-5 * np.abs(o_dgamma).max() + 1e-9
 
 
+@pytest.mark.parametrize("shape", [(3, 64), (1001, 896), (130, 4096), (5, 8192)])
+def test_rmsnorm_residual_form_matches_oracle(B, shape):
+    """Fused residual add: the stored residual stream h is the oracle's bf16 sum bit for bit
+    (byte work: one rounding of an exact or harmlessly rounded fp32 sum); y, rstd and the
+    gradient of h (with a gradient arriving through the residual stream) as for the plain norm."""
+    N, D = shape
+    eps = 1e-6
+    rng = np.random.default_rng(N * 7 + D)
+    x, gamma, dy = _norm_case(N, D, seed=N + D + 1)
+    res = I.f32_to_bf16_bits((rng.standard_normal((N, D)) * np.exp(rng.uniform(-8, 3, (N, D)))).astype(np.float32))
+    d_res = I.f32_to_bf16_bits((rng.standard_normal((N, D)) * 2e-3).astype(np.float32))
+    print(f"[rmsnorm+residual] N={N} D={D}", flush=True)
+    xd, rd = bf16_dev(x), bf16_dev(res)
+    y, rstd = B.cce_rmsnorm_residual_forward(xd, rd, bf16_dev(gamma), eps)
+    dh, dgamma = B.cce_rmsnorm_residual_backward(rd, bf16_dev(gamma), rstd, bf16_dev(dy), bf16_dev(d_res))
+    dh0, _ = B.cce_rmsnorm_residual_backward(rd, bf16_dev(gamma), rstd, bf16_dev(dy), None)
+    dx_plain, _ = B.cce_rmsnorm_backward(rd, bf16_dev(gamma), rstd, bf16_dev(dy))
+    torch.cuda.synchronize()
+    o_h, o_y, o_rstd = R.forward_residual(x, res, gamma, eps)
+    h_bits = rd.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(h_bits, o_h)
+    assert np.array_equal(xd.view(torch.int16).cpu().numpy().view(np.uint16), x)          # x untouched
+    assert np.abs(rstd.cpu().numpy() / o_rstd - 1.0).max() <= 2e-6
+    yh = bf16_host(y)
+    assert np.all(np.abs(yh - o_y) <= 2.0 ** -8 * np.abs(o_y) + 1e-6)
+    o_dh, o_dgamma = R.backward_residual(o_h, gamma, dy, eps, d_res)
+    dhh = bf16_host(dh)
+    assert np.all(np.abs(dhh - o_dh) <= 2.0 ** -8 * np.abs(o_dh) + 1e-8)
+    assert np.abs(dgamma.cpu().numpy() - o_dgamma).max() <= 1e-5 * np.abs(o_dgamma).max() + 1e-9
+    assert torch.equal(dh0, dx_plain)                      # no residual gradient: the plain backward
+    assert rel_fro(dhh - bf16_host(dh0), I.bf16_bits_to_f32(d_res).astype(np.float64)) <= 2e-2
+
+
 def test_rmsnorm_dgamma_accumulates_and_is_reproducible(B):
     x, gamma, dy = _norm_case(700, 896, seed=3)
     xd, gd, dyd = bf16_dev(x), bf16_dev(gamma), bf16_dev(dy)

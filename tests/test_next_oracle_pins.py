@@ -30,6 +30,48 @@ def _case(N=7, D=12, seed=0):
 
 
 # ------------------------------------------------------------------ RMSNorm
+def test_round_bf16_matches_torch_and_breaks_ties_to_even():
+    rng = np.random.default_rng(3)
+    v = (rng.standard_normal(100000) * np.exp(rng.uniform(-20, 20, 100000))).astype(np.float32).astype(np.float64)
+    ref = torch.from_numpy(v.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(R.round_bf16(v), ref)
+    b = np.arange(0x3F80, 0x3FA0, dtype=np.uint32)
+    lo = (b << 16).view(np.float32).astype(np.float64)
+    hi = ((b + 1) << 16).astype(np.uint32).view(np.float32).astype(np.float64)
+    assert np.array_equal(R.round_bf16((lo + hi) / 2), np.where(b % 2 == 0, b, b + 1).astype(np.uint16))
+    assert np.array_equal(R.round_bf16(-(lo + hi) / 2), (np.where(b % 2 == 0, b, b + 1) | 0x8000).astype(np.uint16))
+    # a value a hair above a tie goes up even when float32 cannot tell it from the tie
+    assert R.round_bf16(np.array([(lo[0] + hi[0]) / 2 * (1 + 2.0 ** -40)]))[0] == b[0] + 1
+
+
+def test_rmsnorm_residual_form():
+    """h is torch's own bf16 sum (fp32 add, one rounding); y and the gradients are those of the
+    plain norm applied to h; x and the residual receive the same gradient, plus what arrives
+    through the residual stream."""
+    rng = np.random.default_rng(4)
+    x, gamma, dy = _case(N=9, D=16, seed=5)
+    res = _bits(rng.standard_normal((9, 16)) * np.exp(rng.uniform(-6, 3, (9, 16))))
+    h_bits, y, rstd = R.forward_residual(x, res, gamma, 1e-5)
+    tx = torch.from_numpy(x.view(np.int16)).view(torch.bfloat16)
+    tr = torch.from_numpy(res.view(np.int16)).view(torch.bfloat16)
+    assert np.array_equal(h_bits, (tx + tr).view(torch.int16).numpy().view(np.uint16))
+    y0, rstd0 = R.forward(h_bits, gamma, 1e-5)
+    assert np.array_equal(y, y0) and np.array_equal(rstd, rstd0)
+    # gradient through the fused form, by autograd on float64 copies of x and residual whose sum is h
+    hx = torch.tensor(_f64(h_bits) - _f64(res), requires_grad=True)
+    hr = torch.tensor(_f64(res), requires_grad=True)
+    gt = torch.tensor(_f64(gamma), requires_grad=True)
+    h = hx + hr
+    out = torch.nn.functional.rms_norm(h, (16,), gt, 1e-5)
+    d_res_in = _bits(rng.standard_normal((9, 16)) * 0.02)
+    (out * torch.tensor(_f64(dy))).sum().backward(retain_graph=True)
+    (h * torch.tensor(_f64(d_res_in))).sum().backward()
+    dh, dgamma = R.backward_residual(h_bits, gamma, dy, 1e-5, d_res_in)
+    assert np.allclose(dh, hx.grad.numpy(), atol=1e-14, rtol=0) and np.allclose(dh, hr.grad.numpy(), atol=1e-14, rtol=0)
+    assert np.allclose(dgamma, gt.grad.numpy(), atol=1e-14, rtol=0)
+    dh0, _ = R.backward_residual(h_bits, gamma, dy, 1e-5)
+    assert np.allclose(dh - dh0, _f64(d_res_in), atol=1e-15)
+
 
 @pytest.mark.parametrize("eps", [1e-6, 1e-2])
 def test_rmsnorm_against_torch_and_autograd(eps):
