@@ -225,6 +225,7 @@ def main() -> int:
         O.backward(w.hidden[:rows], w.weight, w.labels[:rows], w.dloss_mean[:rows], w.spec.ignore_index)
         dt = time.perf_counter() - t0
         cpu = {"value": round(rows / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "fp64_gflops_6NVD": round(6.0 * rows * V * D / dt / 1e9, 1),
                "sample": f"fp64 oracle forward+backward on the first {rows} of {N} rows with the full "
                          f"V={V} vocabulary ({dt:.1f} s wall)"}
 
@@ -235,6 +236,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={N} D={D} V={V}, {w.spec.ignore_frac:.0%} ignore_index, "
                                f"seed {w.spec.seed}", "n_valid": n_valid},
+        "valid_tokens_per_s": round(n_valid / (ms_per_step * 1e-3), 1),
         "tflops_executed_8NVD": round(executed_tflops, 1),
         "tflops_model_6NVD": round(6 * nvd / (ms_per_step * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100 * executed_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
