@@ -38,10 +38,11 @@
  *     aborts across this boundary.  On an error return nothing was enqueued.
  *   - `workspace` is caller-owned device scratch of at least
  *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
- *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, the lower
- *     halves of the fp32 dHidden sums of one row block (their upper halves live in
- *     dHidden itself until the last vocabulary chunk rounds the sums to bf16 there) and
- *     one bf16 [row block x vocab chunk] gradient chunk; it never scales with N*V.  Contents are scratch: nothing
+ *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, the fp32
+ *     dHidden sums of one row block (for large D only their lower halves: the upper
+ *     halves then live in dHidden itself until the last vocabulary chunk rounds the
+ *     sums to bf16 there) and one bf16 [row block x vocab chunk] gradient chunk; it
+ *     never scales with N*V.  Contents are scratch: nothing
  *     needs to survive between forward and backward except what the caller
  *     passes explicitly (lse).
  */

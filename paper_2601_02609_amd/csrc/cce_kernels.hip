@@ -534,14 +534,16 @@ constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
 constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, TileBig::BN);
 constexpr int kGemmLdsNarrow = gemm_lds_bytes(TileNarrow::kLdsBytes, TileNarrow::BM, TileNarrow::BN);
 
-// Output of a job, one of two forms:
+// Output of a job, one of three forms:
 //   fp32 (the dW job): out_f32 (+)= C when `beta`.
-//   split (the dH job, out_f32 == nullptr): the fp32 running sum over the vocabulary chunks is
-//   kept as two 16-bit planes -- the upper halves of the fp32 words in the bf16 output tensor
-//   itself (out_hi, the caller's dHidden, whose final content is written by the last chunk), the
-//   lower halves in the workspace (out_lo) -- so that the accumulator costs 2 instead of 4
-//   workspace bytes per element; the split is exact.  `beta`: add to the stored sum; `final`:
-//   round the sum to bf16 into out_hi instead of storing the two planes.
+//   fp32 running sum + bf16 result (the dH job): out_f32 is a workspace accumulator over the
+//   vocabulary chunks; on the `final` chunk the sum is rounded to bf16 into out_hi (dHidden).
+//   split running sum (the dH job, out_lo given): the fp32 sum is kept as two 16-bit planes --
+//   the upper halves of the fp32 words in the bf16 output tensor itself (out_hi, whose final
+//   content is written by the last chunk), the lower halves in the workspace (out_lo) -- so
+//   that the accumulator costs 2 instead of 4 workspace bytes per element; the split is exact.
+//   It costs ~2 us per launch (8-byte instead of 16-byte accesses) and is used only where the
+//   smaller accumulator buys a better tiling.
 struct GemmJob {
     int a_kmajor;               // 1: A is K-major (the dH job), 0: A is K-slow (the dW job)
     const uint16_t* A; int lda; int a_free_n; int a_k_n;
@@ -551,7 +553,9 @@ struct GemmJob {
     uint16_t* out_hi; uint16_t* out_lo; int final;
 };
 
-template <class Cfg, bool A_KMAJOR>
+// SPLIT: the launch's dH job uses the split running sum (a launch-wide constant, compiled as a
+// separate kernel so that the plain form carries none of its code).
+template <class Cfg, bool A_KMAJOR, bool SPLIT>
 __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS char* smem) {
     const int mi = item / j.n_tiles, ni = item % j.n_tiles;    // consecutive items share the A band
 
@@ -594,7 +598,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     // the previous pass -- so that their latency hides under the staging through LDS
     // (whose barriers wait for LDS traffic only).
     // (split form: words 0-1 of old[] hold the upper-half plane, words 2-3 the lower-half plane)
-    const bool split = j.out_f32 == nullptr;
+    const bool split = SPLIT && j.out_lo != nullptr;
     f32x4 old[kIters];
     auto fetch_old = [&](int pr0) {
 #pragma unroll
@@ -670,13 +674,13 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
         for (int it = 0; it < kIters; ++it) {
             const int row = mi * Cfg::BM + pr0 + it * kRowsPerIter + my_row;
             if (!col_ok || row >= j.m_valid) continue;
-            if (!split) {
-                *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
-            } else if (j.final) {
+            if (j.final) {
                 union { __bf16 h[4]; u32x2 u; } cv;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[it][e];
                 *(u32x2*)(j.out_hi + (size_t)row * j.ld_out + col) = cv.u;
+            } else if (!split) {
+                *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
             } else {
                 const u32x4 b = __builtin_bit_cast(u32x4, v[it]);
                 const u32x2 hi = {(b.y & 0xffff0000u) | (b.x >> 16), (b.w & 0xffff0000u) | (b.z >> 16)};
@@ -692,7 +696,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     }
 }
 
-template <class Cfg>
+template <class Cfg, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first, const GemmJob second) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -700,8 +704,8 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
     const bool in_first = lin < first.n_work;
     const GemmJob& j = in_first ? first : second;
     const int item = in_first ? lin : lin - first.n_work;
-    if (j.a_kmajor) run_gemm_job<Cfg, true>(j, item, smem);
-    else run_gemm_job<Cfg, false>(j, item, smem);
+    if (j.a_kmajor) run_gemm_job<Cfg, true, SPLIT>(j, item, smem);
+    else run_gemm_job<Cfg, false, false>(j, item, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -760,6 +764,7 @@ struct Plan {
     int TT, VT, S;              // forward: token tiles, vocabulary tiles, vocabulary splits
     int64_t Nb, Vc;             // backward: rows per row block, vocabulary columns per chunk (multiples of 256)
     int gemm_kind;              // backward: output tile of the contractions, 0 = 256 x 256, 1 = 256 x 128
+    int split_acc;              // backward: dH running sum as two 16-bit planes (see GemmJob)
     size_t off_status, off_partials, off_sumz, off_dhacc, off_g, total;
 };
 
@@ -869,16 +874,17 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     const size_t fixed = 256 + partial_bytes;
 
     // Row block of a tiles, vocabulary chunk of b tiles.
+    int acc_bytes = 4;          // per element of the dH running sum: 4 (fp32) or 2 (split planes)
     auto bytes_needed = [&](int64_t a, int64_t b) {
-        return (double)fixed + (double)round_up(a * 256 * D * 2, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
+        return (double)fixed + (double)round_up(a * 256 * D * acc_bytes, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
     };
     // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
-    auto plan_for_kind = [&](int kind, int* a_out, int* b_out) {
+    auto plan_for_kind = [&](int kind, int* a_out, int* b_out) -> double {
         BackwardModel model{cus, D, gemm_tile_of_kind(kind)};
         if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
             *a_out = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
             *b_out = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
-            return;
+            return 0.0;
         }
         double best_cost = 1e300;
         const int a_max = p->TT < 64 ? p->TT : 64, b_max = p->VT < 128 ? p->VT : 128;
@@ -897,23 +903,37 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
                 if (cost < best_cost) { best_cost = cost; *a_out = a; *b_out = b; }
             }
         }
+        return best_cost;
     };
     // 256 x 256 tiles when D is a multiple of 256 and they fill the rounds of `cus` workgroups
     // of a contraction launch to at least 70 %; else 256 x 128.  (The cost model ranks tilings
     // of one tile shape well but is off by ~15 % between the shapes, so the shape is decided
     // by occupancy: measured, D = 1024 and 2048 gain 17 % with the narrow tile, D = 1536 with
     // 77 % occupancy loses 6 %.)
-    int best_a = 1, best_b = 1, best_kind = 1;
-    if (g_force_gemm_cols != 0) {
-        best_kind = g_force_gemm_cols == 256 ? 0 : 1;
-        if (best_kind == 0) plan_for_kind(0, &best_a, &best_b);
-    } else if (D % 256 == 0) {
-        plan_for_kind(0, &best_a, &best_b);
-        const int64_t tiles = (int64_t)(best_a + best_b) * (D / 256);
-        const int64_t rounds = (tiles + cus - 1) / cus;
-        best_kind = (double)tiles >= 0.7 * (double)(rounds * cus) ? 0 : 1;
-    }
-    if (best_kind == 1) plan_for_kind(1, &best_a, &best_b);
+    auto plan_for_acc = [&](int bytes, int* a_out, int* b_out, int* kind_out) -> double {
+        acc_bytes = bytes;
+        double cost = 0.0;
+        *kind_out = 1;
+        if (g_force_gemm_cols != 0) {
+            *kind_out = g_force_gemm_cols == 256 ? 0 : 1;
+            if (*kind_out == 0) cost = plan_for_kind(0, a_out, b_out);
+        } else if (D % 256 == 0) {
+            cost = plan_for_kind(0, a_out, b_out);
+            const int64_t tiles = (int64_t)(*a_out + *b_out) * (D / 256);
+            const int64_t rounds = (tiles + cus - 1) / cus;
+            *kind_out = (double)tiles >= 0.7 * (double)(rounds * cus) ? 0 : 1;
+        }
+        if (*kind_out == 1) cost = plan_for_kind(1, a_out, b_out);
+        return cost;
+    };
+    // The dH running sum: plain fp32 unless the split form (half the workspace, a little slower
+    // per launch) buys a tiling that the model rates at least 3 % faster.
+    int best_a = 1, best_b = 1, best_kind = 1, sa = 1, sb = 1, skind = 1;
+    const double cost_f32 = plan_for_acc(4, &best_a, &best_b, &best_kind);
+    const double cost_split = plan_for_acc(2, &sa, &sb, &skind);
+    p->split_acc = 0;
+    if (cost_split < 0.97 * cost_f32) { best_a = sa; best_b = sb; best_kind = skind; p->split_acc = 1; }
+    acc_bytes = p->split_acc ? 2 : 4;
     p->gemm_kind = best_kind;
     p->Nb = (int64_t)best_a * 256;
     p->Vc = (int64_t)best_b * 256;
@@ -923,7 +943,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->off_partials = 256;
     p->off_sumz = p->off_partials + md_bytes;
     p->off_dhacc = p->off_partials + partial_bytes;
-    p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * 2, 256);
+    p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * (p->split_acc ? 2 : 4), 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
     cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, *p, true};
     return true;
@@ -963,8 +983,10 @@ static bool ensure_kernel_attributes() {
     if (!allow_big_lds(lse_partial_kernel<false, true>, TileBig::kLdsBytes)) return false;
     if (!allow_big_lds(grad_tile_kernel<false>, kGradTileLds)) return false;
     if (!allow_big_lds(grad_tile_kernel<true>, kGradTileLds)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig>, kGemmLdsBig)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, false>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, false>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, true>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, true>, kGemmLdsNarrow)) return false;
     done[dev] = true;
     return true;
 }
@@ -1184,8 +1206,9 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dh.B = (const void*)((const uint16_t*)weight + (size_t)st.v0 * D); dh.ldb = (int)D; dh.b_k_n = (int)st.cols;
         dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = st.row_tiles * per256 * d_tiles;
         dh.m_valid = (int)st.rows; dh.n_valid = (int)D;
-        dh.out_f32 = nullptr; dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
-        dh.out_hi = (uint16_t*)dHidden + (size_t)st.r0 * D; dh.out_lo = dh_lo; dh.final = st.last_chunk ? 1 : 0;
+        dh.out_f32 = p.split_acc ? (float*)nullptr : (float*)(ws + p.off_dhacc); dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
+        dh.out_hi = (uint16_t*)dHidden + (size_t)st.r0 * D; dh.out_lo = p.split_acc ? dh_lo : (uint16_t*)nullptr;
+        dh.final = st.last_chunk ? 1 : 0;
         // dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
         GemmJob dw;
         dw.a_kmajor = 0;
@@ -1202,10 +1225,14 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
 
         {
             ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
-            if (gt.kind == 0)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileBig>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
+            if (gt.kind == 0 && !p.split_acc)
+                hipLaunchKernelGGL((grad_gemm_kernel<TileBig, false>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
+            else if (gt.kind == 0)
+                hipLaunchKernelGGL((grad_gemm_kernel<TileBig, true>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
+            else if (!p.split_acc)
+                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow, false>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
             else
-                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
+                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow, true>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
         }
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
