@@ -175,6 +175,15 @@ int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int
  * Results agree across the two up to fp32 summation order.  Host state only; not thread safe. */
 int cce_set_backward_gemm_tile(int tile_cols);
 
+/* Tuning / testing aid: how the running sum of dHidden over the vocabulary chunks is kept --
+ * 1: fp32 in the workspace; 2: as two 16-bit planes, the upper halves in dHidden itself and
+ * the lower halves in the workspace (half the workspace share, exact, slightly slower per
+ * launch); 0 restores the automatic choice (2 only where it buys a better tiling, i.e. large D).
+ * Results are bit-identical between the two for the same tiling.  Host state only. */
+int cce_set_backward_accumulator(int mode);
+/* The form (1 or 2) used for this shape.  Host only. */
+int cce_get_backward_accumulator(int64_t N, int64_t D, int64_t V, int* mode);
+
 /* Rows x columns of the output tile the two gradient contractions use for this shape (256 x 256
  * or 256 x 128; chosen with the tiling, by the same cost model: the narrow tile when a chunk's
  * outputs would otherwise be too few tiles to fill the GPU, or when D is not a multiple of 256).

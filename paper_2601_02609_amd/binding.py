@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = [
     "cce_forward_ex", "cce_backward_ex",
     "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
     "cce_get_backward_tiling", "cce_get_backward_gemm_tile", "cce_set_backward_gemm_tile",
+    "cce_set_backward_accumulator", "cce_get_backward_accumulator",
     # include/cce_aux.h
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
     "cce_rmsnorm_residual_forward", "cce_rmsnorm_residual_backward",
@@ -90,6 +91,10 @@ def lib() -> ctypes.CDLL:
     L.cce_set_backward_tiling.argtypes = [ctypes.c_int, ctypes.c_int]
     L.cce_get_backward_tiling.restype = ctypes.c_int
     L.cce_get_backward_tiling.argtypes = [i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
+    L.cce_set_backward_accumulator.restype = ctypes.c_int
+    L.cce_set_backward_accumulator.argtypes = [ctypes.c_int]
+    L.cce_get_backward_accumulator.restype = ctypes.c_int
+    L.cce_get_backward_accumulator.argtypes = [i64, i64, i64, ctypes.POINTER(ctypes.c_int)]
     L.cce_set_backward_gemm_tile.restype = ctypes.c_int
     L.cce_set_backward_gemm_tile.argtypes = [ctypes.c_int]
     L.cce_get_backward_gemm_tile.restype = ctypes.c_int
@@ -311,6 +316,21 @@ def get_backward_tiling(N: int, D: int, V: int) -> Tuple[int, int]:
     if rc != CCE_OK:
         raise CCEError(rc, "cce_get_backward_tiling")
     return int(a.value), int(b.value)
+
+
+def set_backward_accumulator(mode: int = 0) -> None:
+    """dHidden running sum: 1 = fp32 in the workspace, 2 = split 16-bit planes, 0 = automatic."""
+    rc = lib().cce_set_backward_accumulator(mode)
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_set_backward_accumulator")
+
+
+def get_backward_accumulator(N: int, D: int, V: int) -> int:
+    m = ctypes.c_int(0)
+    rc = lib().cce_get_backward_accumulator(N, D, V, ctypes.byref(m))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_get_backward_accumulator")
+    return int(m.value)
 
 
 def set_backward_gemm_tile(tile_cols: int = 0) -> None:

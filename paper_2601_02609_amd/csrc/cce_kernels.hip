@@ -788,6 +788,7 @@ static GemmTile gemm_tile_of_kind(int kind) {
 // Backward tiling forced by cce_set_backward_tiling (0 = automatic).
 static int g_force_row_tiles = 0, g_force_vocab_tiles = 0;
 static int g_force_gemm_cols = 0;        // cce_set_backward_gemm_tile: 0 = automatic, 128 or 256
+static int g_force_split_acc = 0;        // cce_set_backward_accumulator: 0 = automatic, 1 = fp32, 2 = split
 
 // Rough time model of the backward pipeline, in microseconds, used only to rank tilings.
 // One compute unit runs one workgroup at a time.  Measured on MI355X with random bf16 data:
@@ -842,10 +843,10 @@ struct BackwardModel {
 
 static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     if (N <= 0 || D <= 0 || V <= 0) return false;
-    struct Key { int64_t N, D, V; int fa, fb, fc; Plan plan; bool valid; };
-    static thread_local Key cache = {0, 0, 0, 0, 0, 0, {}, false};
+    struct Key { int64_t N, D, V; int fa, fb, fc, fs; Plan plan; bool valid; };
+    static thread_local Key cache = {0, 0, 0, 0, 0, 0, 0, {}, false};
     if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.fa == g_force_row_tiles &&
-        cache.fb == g_force_vocab_tiles && cache.fc == g_force_gemm_cols) { *p = cache.plan; return true; }
+        cache.fb == g_force_vocab_tiles && cache.fc == g_force_gemm_cols && cache.fs == g_force_split_acc) { *p = cache.plan; return true; }
 
     const int cus = device_cu_count();
     const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
@@ -932,7 +933,9 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     const double cost_f32 = plan_for_acc(4, &best_a, &best_b, &best_kind);
     const double cost_split = plan_for_acc(2, &sa, &sb, &skind);
     p->split_acc = 0;
-    if (cost_split < 0.97 * cost_f32) { best_a = sa; best_b = sb; best_kind = skind; p->split_acc = 1; }
+    if (g_force_split_acc == 2 || (g_force_split_acc == 0 && cost_split < 0.97 * cost_f32)) {
+        best_a = sa; best_b = sb; best_kind = skind; p->split_acc = 1;
+    }
     acc_bytes = p->split_acc ? 2 : 4;
     p->gemm_kind = best_kind;
     p->Nb = (int64_t)best_a * 256;
@@ -945,7 +948,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->off_dhacc = p->off_partials + partial_bytes;
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * (p->split_acc ? 2 : 4), 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
-    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, *p, true};
+    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, g_force_split_acc, *p, true};
     return true;
 }
 
@@ -1312,6 +1315,21 @@ int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int
 int cce_set_backward_gemm_tile(int tile_cols) {
     if (tile_cols != 0 && tile_cols != 128 && tile_cols != 256) return CCE_ERR_INVALID;
     g_force_gemm_cols = tile_cols;
+    return CCE_OK;
+}
+
+int cce_set_backward_accumulator(int mode) {
+    if (mode < 0 || mode > 2) return CCE_ERR_INVALID;
+    g_force_split_acc = mode;
+    return CCE_OK;
+}
+
+int cce_get_backward_accumulator(int64_t N, int64_t D, int64_t V, int* mode) {
+    Plan p;
+    if (!mode || N <= 0 || D <= 0 || V <= 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (!make_plan(N, D, V, &p)) return CCE_ERR_INVALID;
+    *mode = p.split_acc ? 2 : 1;
     return CCE_OK;
 }
 

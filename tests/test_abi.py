@@ -92,3 +92,12 @@ def test_contraction_tile_choice(L):
         assert binding.get_backward_gemm_tile(32768, 3584, 151936) == (256, 128)
     finally:
         binding.set_backward_gemm_tile(0)
+
+
+def test_accumulator_choice(L):
+    """fp32 running sum at the headline shape (it fits the budget with the best tiling), split
+    planes where D is large against the budget."""
+    assert binding.get_backward_accumulator(8192, 896, 151936) == 1
+    assert binding.get_backward_accumulator(16384, 4096, 32000) == 2
+    with pytest.raises(binding.CCEError):
+        binding.set_backward_accumulator(3)

@@ -118,6 +118,32 @@ def test_backward_with_either_contraction_tile(B, shape, cols):
         B.set_backward_gemm_tile(64)
 
 
+@pytest.mark.parametrize("cols", [128, 256])
+def test_split_accumulator_is_bit_identical(B, cols):
+    """The running sum of dHidden as two 16-bit planes (upper halves in dHidden itself) is an
+    exact split of the fp32 sum: for the same tiling both forms give the same bits, over
+    several vocabulary chunks and row blocks."""
+    w = I.make_workload(I.custom_spec(700, 512, 3000, seed=15, ignore_frac=0.2))
+    try:
+        B.set_backward_tiling(2, 3)
+        B.set_backward_gemm_tile(cols)
+        B.set_backward_accumulator(1)
+        assert B.get_backward_accumulator(700, 512, 3000) == 1
+        ws1 = B.workspace_bytes(700, 512, 3000)
+        base = run_both(B, w, w.dloss_var)
+        B.set_backward_accumulator(2)
+        assert B.get_backward_accumulator(700, 512, 3000) == 2
+        assert B.workspace_bytes(700, 512, 3000) == ws1 - 2 * 256 * 512 * 2
+        check_against_oracle(B, w, w.dloss_var, f"split-acc/256x{cols}")
+        got = run_both(B, w, w.dloss_var)
+    finally:
+        B.set_backward_tiling(0, 0)
+        B.set_backward_gemm_tile(0)
+        B.set_backward_accumulator(0)
+    for a, b in zip(base, got):
+        assert np.array_equal(a, b)
+
+
 def test_single_token_single_class(B):
     w = I.make_workload(I.custom_spec(1, 64, 1, seed=2, ignore_frac=0.0, labels="uniform"))
     loss, lse, dH, dW = run_both(B, w, w.dloss_mean)
