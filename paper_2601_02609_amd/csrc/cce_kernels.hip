@@ -418,30 +418,24 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
 
-    // per-token scalars of this lane's columns, and the liveness of the row this thread will
-    // flag, are fetched before the main loop so that their latency hides under it
-    int32_t col_y[Cfg::TN];
-    float col_sp[Cfg::TN], col_ch[Cfg::TN], col_ncs[Cfg::TN], col_nl2[Cfg::TN];
+    // Per-token scalars of this lane's columns, and the label of the row this thread will flag:
+    // only the raw loads are issued here -- unconditional, from clamped indices, so that there is
+    // no branch the compiler would have to wait behind -- and everything derived from them is
+    // computed after the main loop, under which their latency hides.
+    int32_t raw_y[Cfg::TN], raw_row_y;
+    float raw_dl[Cfg::TN], raw_ls[Cfg::TN];
     const float uniform_dl = dloss ? 0.f : mean_scale[0];
-    const float eps_over_v = label_smoothing / (float)V_total;
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn) {
         const int tok = tok0 + acc_col<Cfg>(bn);
-        const bool tok_ok = tok < N;
-        // label as a row of W (W holds the rows [v_off, v_off + V) of a V_total-row matrix)
-        const int64_t y_local = tok_ok ? (int64_t)labels[tok] - v_off : -1;
-        col_y[bn] = (y_local >= 0 && y_local < V) ? (int32_t)y_local : -1;
-        const float dl = tok_ok ? (dloss ? dloss[tok] : uniform_dl) : 0.f;
-        const float ls = tok_ok ? lse[tok] : 0.f;
-        col_sp[bn] = dl * fmaf(2.f * z_loss, ls, 1.f);      // factor of the softmax term
-        col_ch[bn] = dl * (1.f - label_smoothing);          // subtracted at the label
-        col_ncs[bn] = -dl * eps_over_v;                     // added everywhere
-        col_nl2[bn] = -ls * kLog2e;
+        const int t = tok < N ? tok : N - 1;
+        raw_y[bn] = labels[t];
+        raw_dl[bn] = dloss ? dloss[t] : uniform_dl;
+        raw_ls[bn] = lse[t];
     }
-    bool row_live = false;
-    if (threadIdx.x < Cfg::BN && tok0 + (int)threadIdx.x < N) {
-        const int32_t y = labels[tok0 + threadIdx.x];
-        row_live = (y != ignore_index) && (y >= 0) && (y < V_total);
+    {
+        const int tok = tok0 + (int)(threadIdx.x & (Cfg::BN - 1));
+        raw_row_y = labels[tok < N ? tok : N - 1];
     }
 
     OperandTile<true, Cfg::BM> Aop;
@@ -458,6 +452,25 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     } else {
         gemm_mainloop<Cfg, true, true>(acc, Aop, Bop, D, smem);
     }
+
+    int32_t col_y[Cfg::TN];
+    float col_sp[Cfg::TN], col_ch[Cfg::TN], col_ncs[Cfg::TN], col_nl2[Cfg::TN];
+    const float eps_over_v = label_smoothing / (float)V_total;
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+        const bool tok_ok = tok0 + acc_col<Cfg>(bn) < N;
+        // label as a row of W (W holds the rows [v_off, v_off + V) of a V_total-row matrix)
+        const int64_t y_local = tok_ok ? (int64_t)raw_y[bn] - v_off : -1;
+        col_y[bn] = (y_local >= 0 && y_local < V) ? (int32_t)y_local : -1;
+        const float dl = tok_ok ? raw_dl[bn] : 0.f;
+        const float ls = tok_ok ? raw_ls[bn] : 0.f;
+        col_sp[bn] = dl * fmaf(2.f * z_loss, ls, 1.f);      // factor of the softmax term
+        col_ch[bn] = dl * (1.f - label_smoothing);          // subtracted at the label
+        col_ncs[bn] = -dl * eps_over_v;                     // added everywhere
+        col_nl2[bn] = -ls * kLog2e;
+    }
+    const bool row_live = threadIdx.x < Cfg::BN && tok0 + (int)threadIdx.x < N &&
+                          raw_row_y != ignore_index && raw_row_y >= 0 && raw_row_y < V_total;
 
     CCE_LDS unsigned char* live_flags = (CCE_LDS unsigned char*)(smem + 256 * kGRowBytes);
     if (threadIdx.x < Cfg::BN) live_flags[threadIdx.x] = row_live ? 1 : 0;
