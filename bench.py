@@ -201,6 +201,21 @@ def main() -> int:
                "backward_us": round(b_us, 1)}
         del hq, hsc, wq, wsc
 
+    # Row skipping (include/cce_compact.h): the same step through the entry points that take the
+    # number of valid rows from the host (counted here from the host copy of the labels, as a
+    # data loader would) and leave the ignored rows out of every product.  Not `value`.
+    n_valid_host = int(((w.labels != w.spec.ignore_index) & (w.labels >= 0) & (w.labels < V)).sum())
+    wc = B.alloc_compact_workspace(N, D, V, n_valid_host)
+    def compact_step():
+        B.cce_forward_compact(H, W, y, n_valid_host, w.spec.ignore_index, workspace=wc, loss=loss, lse=lse)
+        B.cce_backward_compact(H, W, y, lse, dl, n_valid_host, w.spec.ignore_index, workspace=wc, d_hidden=dH, d_weight=dW)
+    c_us = timed_us(compact_step, reps=10)
+    skip = {"rows_skipped": bool(B.get_row_skipping(N, D, V, n_valid_host)), "valid_rows": n_valid_host,
+            "ms_per_step": round(c_us * 1e-3, 4), "tokens_per_s": round(N / (c_us * 1e-6), 1),
+            "tflops_executed_8NvalidVD": round(8.0 * n_valid_host * V * D / (c_us * 1e-6) / 1e12, 1),
+            "workspace_bytes": int(wc.numel())}
+    del wc
+
     # what the peak is divided by: the nominal figure, the one the device properties give
     # (compute units x 4096 flop/clock x clock), and a register-only MFMA loop on this device
     cus, khz = B.device_info()
@@ -244,7 +259,7 @@ def main() -> int:
         "workspace_pct_of_logits": round(100.0 * ws.numel() / B.materialised_logit_bytes(N, V), 3),
         "backward_tiling_256": list(B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
-        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "mfma_peak": peak_info,
+        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "row_skipping": skip, "mfma_peak": peak_info,
     }
     print(json.dumps(out))
     return 0

@@ -64,7 +64,8 @@ enum {
 };
 
 enum {
-    CCE_STATUS_BAD_LABEL = 1   /* some label was outside [0, V) and not ignore_index */
+    CCE_STATUS_BAD_LABEL = 1,  /* some label was outside [0, V) and not ignore_index */
+    CCE_STATUS_ROW_BOUND = 2   /* cce_*_compact: more valid rows than max_valid_rows; results are incomplete */
 };
 
 /* Library version, "major.minor.patch". Host only. */
@@ -158,7 +159,7 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
  * vocabulary chunks of `vocab_tiles` x 256 columns (clamped to the problem size) for all
  * later calls of this process, cce_workspace_bytes included; (0, 0) restores the automatic
  * choice, which stays inside the workspace budget (1 % of the materialised logits, at
- * least 48 MiB).  The chunking is a free parameter of the chunk-level backward
+ * least 48 MB).  The chunking is a free parameter of the chunk-level backward
  * algorithm: results agree across tilings up to fp32 summation order.  Host state only;
  * not thread safe.  Returns CCE_ERR_INVALID for negative values or when only one is 0.  A forced
  * tiling whose gradient chunk (rows x columns x 2 bytes) would reach 4 GiB makes the calls that

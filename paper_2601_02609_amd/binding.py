@@ -34,6 +34,9 @@ EXPORTED_SYMBOLS = [
     "cce_mfma_probe", "cce_device_info",
     # include/cce_shard.h
     "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
+    # include/cce_compact.h
+    "cce_compact_workspace_bytes", "cce_forward_compact", "cce_backward_compact",
+    "cce_get_row_skipping", "cce_set_row_skipping",
     # include/cce_fp8.h
     "cce_fp8_scale_bytes", "cce_quantize_e4m3", "cce_fp8_forward", "cce_fp8_backward",
 ]
@@ -128,6 +131,16 @@ def lib() -> ctypes.CDLL:
     L.cce_shard_backward.restype = ctypes.c_int
     L.cce_shard_backward.argtypes = [vp, vp, vp, vp, vp, f32, i64, i64, i64, i64, i64, i32, f32, f32,
                                      vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_get_row_skipping.restype = ctypes.c_int
+    L.cce_get_row_skipping.argtypes = [i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int)]
+    L.cce_set_row_skipping.restype = ctypes.c_int
+    L.cce_set_row_skipping.argtypes = [ctypes.c_int]
+    L.cce_compact_workspace_bytes.restype = sz
+    L.cce_compact_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.cce_forward_compact.restype = ctypes.c_int
+    L.cce_forward_compact.argtypes = [vp, vp, vp, i64, i64, i64, i32, i64, vp, vp, vp, sz, vp]
+    L.cce_backward_compact.restype = ctypes.c_int
+    L.cce_backward_compact.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i64, vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_fp8_scale_bytes.restype = sz
     L.cce_fp8_scale_bytes.argtypes = [i64, i64]
     L.cce_quantize_e4m3.restype = ctypes.c_int
@@ -707,4 +720,83 @@ def cce_fp8_backward(hidden_q: torch.Tensor, hidden_scales: torch.Tensor, weight
                                lse.data_ptr(), dloss.data_ptr(), N, D, V, ignore_index,
                                d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
                                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_fp8_backward")
+    return d_hidden, d_weight
+
+
+# ---------------------------------------------------------------- include/cce_compact.h
+
+def compact_workspace_bytes(N: int, D: int, V: int, max_valid_rows: int) -> int:
+    return int(lib().cce_compact_workspace_bytes(N, D, V, max_valid_rows))
+
+
+def set_row_skipping(mode: int = 0) -> None:
+    """1 = never skip rows, 2 = skip whenever the bound is below N, 0 = automatic."""
+    _rc(lib().cce_set_row_skipping(mode), "cce_set_row_skipping")
+
+
+def get_row_skipping(N: int, D: int, V: int, max_valid_rows: int) -> bool:
+    m = ctypes.c_int(0)
+    _rc(lib().cce_get_row_skipping(N, D, V, max_valid_rows, ctypes.byref(m)), "cce_get_row_skipping")
+    return bool(m.value)
+
+
+def alloc_compact_workspace(N: int, D: int, V: int, max_valid_rows: int, device="cuda") -> torch.Tensor:
+    n = compact_workspace_bytes(N, D, V, max_valid_rows)
+    if n == 0:
+        raise CCEError(CCE_ERR_UNSUPPORTED, "cce_compact_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def cce_forward_compact(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor, max_valid_rows: int,
+                        ignore_index: int = -100, *, workspace: Optional[torch.Tensor] = None,
+                        loss: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """cce_forward over the valid rows only (max_valid_rows: host upper bound on their number)."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_compact_workspace(N, D, V, max_valid_rows, hidden.device)
+    if loss is None:
+        loss = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    _rc(lib().cce_forward_compact(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), N, D, V, ignore_index,
+                                  max_valid_rows, loss.data_ptr(), lse.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_forward_compact")
+    return loss, lse
+
+
+def cce_backward_compact(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor, lse: torch.Tensor,
+                         dloss: torch.Tensor, max_valid_rows: int, ignore_index: int = -100, *,
+                         workspace: Optional[torch.Tensor] = None,
+                         d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                         accumulate_dw: bool = False,
+                         stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """cce_backward over the valid rows only."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_compact_workspace(N, D, V, max_valid_rows, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(V, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (V, D), "d_weight")
+    _rc(lib().cce_backward_compact(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), lse.data_ptr(),
+                                   dloss.data_ptr(), N, D, V, ignore_index, max_valid_rows,
+                                   d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_backward_compact")
     return d_hidden, d_weight

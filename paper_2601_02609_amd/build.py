@@ -14,7 +14,8 @@ HEADERS = [os.path.join(CSRC, "gemm_core.h"), os.path.join(CSRC, "host_util.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce_aux.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce_shard.h"),
-           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_fp8.h")]
+           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_fp8.h"),
+           os.path.join(os.path.dirname(PKG_DIR), "include", "cce_compact.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -22,6 +22,7 @@
 #include "../../include/cce.h"
 #include "../../include/cce_shard.h"
 #include "../../include/cce_fp8.h"
+#include "../../include/cce_compact.h"
 #include "gemm_core.h"
 #include "host_util.h"
 
@@ -101,7 +102,7 @@ template <bool SUMZ, bool FP8>
 __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
         const void* __restrict__ H, const void* __restrict__ W,
         int N, int D, int V, int TT, int VT, int S, float2* __restrict__ partials,
-        float* __restrict__ partial_sumz, const Fp8Scales fp8) {
+        float* __restrict__ partial_sumz, const Fp8Scales fp8, const int32_t* __restrict__ perm) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void lse_partial_kernel(
 
     const int ld = FP8 ? D / 2 : D;               // row length in 2-byte units
     OperandTile<true, Cfg::BN> Bop;
-    Bop.init(H, ld, tt * Cfg::BN, N, ld);
+    Bop.init(H, ld, tt * Cfg::BN, N, ld, perm);       // perm: token t of the tile space is row perm[t] of H
     ScaleGroup SB;
     const int b_row0 = tt * Cfg::BN + wave_n<Cfg>() * (Cfg::TN * 32);      // this wavefront's first token
     if (FP8) SB.init(fp8.hscale, fp8.hgroups, b_row0 >> 7);
@@ -230,10 +231,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(
         const float2* __restrict__ partials, const float* __restrict__ partial_sumz,
         int N, int D, int V, int S, int32_t ignore_index, float label_smoothing, float z_loss,
         float* __restrict__ loss, float* __restrict__ lse, int32_t* __restrict__ status,
-        int v_off, float4* __restrict__ stats, const Fp8Scales fp8) {
+        int v_off, float4* __restrict__ stats, const Fp8Scales fp8, const int32_t* __restrict__ perm) {
     const int l = threadIdx.x & 63;
-    const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tok >= N) return;
+    const int ctok = blockIdx.x * 4 + (threadIdx.x >> 6);     // token of the (compact) tile space
+    if (ctok >= N) return;
+    // row skipping: partials are indexed by the compact token, everything else by the original row
+    const int tok = perm ? perm[ctok] : ctok;
+    if (tok < 0) return;
     const int64_t y_local = (int64_t)labels[tok] - v_off;
     const int32_t y = (y_local >= 0 && y_local < V) ? (int32_t)y_local : -1;     // row of W, or none
     const bool in_range = y >= 0;
@@ -247,9 +251,9 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     }
     float m = -INFINITY, d = 0.f, sumz = 0.f;
     for (int i = l; i < S; i += 64) {
-        const float2 p = partials[(size_t)tok * S + i];
+        const float2 p = partials[(size_t)ctok * S + i];
         md_merge(m, d, p.x, p.y);
-        if (partial_sumz) sumz += partial_sumz[(size_t)tok * S + i];
+        if (partial_sumz) sumz += partial_sumz[(size_t)ctok * S + i];
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
@@ -564,11 +568,13 @@ struct GemmJob {
     int n_tiles; int n_work; int m_valid; int n_valid;
     float* out_f32; int64_t ld_out; int beta;
     uint16_t* out_hi; uint16_t* out_lo; int final;
+    const int32_t* row_map;     // row skipping: out_hi row of tile row r is row_map[r] (-1: none); else nullptr
 };
 
-// SPLIT: the launch's dH job uses the split running sum (a launch-wide constant, compiled as a
-// separate kernel so that the plain form carries none of its code).
-template <class Cfg, bool A_KMAJOR, bool SPLIT>
+// MODE bit 0: the launch's dH job uses the split running sum; bit 1: its bf16 rows go through
+// row_map (row skipping).  Launch-wide constants, compiled as separate kernels so that the plain
+// form carries none of their code.
+template <class Cfg, bool A_KMAJOR, int MODE>
 __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS char* smem) {
     const int mi = item / j.n_tiles, ni = item % j.n_tiles;    // consecutive items share the A band
 
@@ -611,7 +617,10 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     // the previous pass -- so that their latency hides under the staging through LDS
     // (whose barriers wait for LDS traffic only).
     // (split form: words 0-1 of old[] hold the upper-half plane, words 2-3 the lower-half plane)
+    constexpr bool SPLIT = (MODE & 1) != 0, ROWMAP = (MODE & 2) != 0;
     const bool split = SPLIT && j.out_lo != nullptr;
+    // row of out_hi that tile row `row` goes to (-1: a padding row of the compact row space)
+    auto hi_row = [&](int row) { return ROWMAP && j.row_map ? j.row_map[row] : row; };
     f32x4 old[kIters];
     auto fetch_old = [&](int pr0) {
 #pragma unroll
@@ -620,7 +629,8 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
             old[it] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (j.beta && col_ok && row < j.m_valid) {
                 if (split) {
-                    const u32x2 hi = *(const u32x2*)(j.out_hi + (size_t)row * j.ld_out + col);
+                    const int orow = hi_row(row);
+                    const u32x2 hi = orow >= 0 ? *(const u32x2*)(j.out_hi + (size_t)orow * j.ld_out + col) : u32x2{0u, 0u};
                     const u32x2 lo = *(const u32x2*)(j.out_lo + (size_t)row * j.ld_out + col);
                     old[it] = __builtin_bit_cast(f32x4, u32x4{hi.x, hi.y, lo.x, lo.y});
                 } else {
@@ -691,14 +701,16 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
                 union { __bf16 h[4]; u32x2 u; } cv;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) cv.h[e] = (__bf16)v[it][e];
-                *(u32x2*)(j.out_hi + (size_t)row * j.ld_out + col) = cv.u;
+                const int orow = hi_row(row);
+                if (orow >= 0) *(u32x2*)(j.out_hi + (size_t)orow * j.ld_out + col) = cv.u;
             } else if (!split) {
                 *(f32x4*)(j.out_f32 + (size_t)row * j.ld_out + col) = v[it];
             } else {
                 const u32x4 b = __builtin_bit_cast(u32x4, v[it]);
                 const u32x2 hi = {(b.y & 0xffff0000u) | (b.x >> 16), (b.w & 0xffff0000u) | (b.z >> 16)};
                 const u32x2 lo = {(b.y << 16) | (b.x & 0xffffu), (b.w << 16) | (b.z & 0xffffu)};
-                *(u32x2*)(j.out_hi + (size_t)row * j.ld_out + col) = hi;
+                const int orow = hi_row(row);
+                if (orow >= 0) *(u32x2*)(j.out_hi + (size_t)orow * j.ld_out + col) = hi;
                 *(u32x2*)(j.out_lo + (size_t)row * j.ld_out + col) = lo;
             }
         }
@@ -709,7 +721,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     }
 }
 
-template <class Cfg, bool SPLIT>
+template <class Cfg, int MODE>
 __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first, const GemmJob second) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -717,8 +729,114 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
     const bool in_first = lin < first.n_work;
     const GemmJob& j = in_first ? first : second;
     const int item = in_first ? lin : lin - first.n_work;
-    if (j.a_kmajor) run_gemm_job<Cfg, true, SPLIT>(j, item, smem);
-    else run_gemm_job<Cfg, false, false>(j, item, smem);
+    if (j.a_kmajor) run_gemm_job<Cfg, true, MODE>(j, item, smem);
+    else run_gemm_job<Cfg, false, 0>(j, item, smem);
+}
+
+// ------------------------------------------------------------------------------------------
+// Row skipping (label scan of the path's first step: rows whose label is ignore_index take no
+// part in any product, so they need not be computed at all).  The valid rows are gathered, in
+// order, into a compact row space in which the unchanged kernels run; results are scattered
+// back.  perm[r] = original row of compact row r, -1 for the padding behind the last valid one.
+// ------------------------------------------------------------------------------------------
+// One workgroup of 1024 threads: stable compaction of the valid rows (label in [0, V) and not
+// ignore_index).  At most max_rows are kept (more: CCE_STATUS_ROW_BOUND, the rest is dropped).
+// loss / lse of the rows that are not valid are set to zero when the pointers are given.
+__global__ __launch_bounds__(1024) void row_scan_kernel(
+        const int32_t* __restrict__ labels, int N, int V, int32_t ignore_index, int max_rows, int rows_pad,
+        int32_t* __restrict__ perm, int32_t* __restrict__ count_out, int32_t* __restrict__ status,
+        float* __restrict__ loss, float* __restrict__ lse) {
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int per = (N + 1023) / 1024;
+    const int i0 = tid * per < N ? tid * per : N, i1 = i0 + per < N ? i0 + per : N;
+    int c = 0, bad = 0;
+    for (int i = i0; i < i1; ++i) {
+        const int32_t y = labels[i];
+        const bool in_range = y >= 0 && y < V;
+        c += (y != ignore_index && in_range) ? 1 : 0;
+        bad |= (y != ignore_index && !in_range) ? 1 : 0;
+    }
+    part[tid] = c;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {            // inclusive scan
+        const int v = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int pos = part[tid] - c;                          // exclusive prefix
+    const int total = part[1023];
+    for (int i = i0; i < i1; ++i) {
+        const int32_t y = labels[i];
+        if (y != ignore_index && y >= 0 && y < V) {
+            if (pos < max_rows) perm[pos] = i;
+            ++pos;
+        } else if (loss) {
+            loss[i] = 0.f;
+            lse[i] = 0.f;
+        }
+    }
+    const int kept = total < max_rows ? total : max_rows;
+    for (int r = kept + tid; r < rows_pad; r += 1024) perm[r] = -1;
+    if (bad) atomicOr(status, CCE_STATUS_BAD_LABEL);
+    if (tid == 0) {
+        count_out[0] = kept;
+        if (total > max_rows) atomicOr(status, CCE_STATUS_ROW_BOUND);
+    }
+}
+
+// out[r, :] = src[perm[r0 + r], :] for r < rows (zeros where perm is -1).  One wavefront per row.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __restrict__ src, const int32_t* __restrict__ perm,
+                                                          int r0, int rows, int D, uint16_t* __restrict__ out) {
+    const int l = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int from = perm[r0 + r];
+    const u32x4* sr = (const u32x4*)(src + (size_t)(from < 0 ? 0 : from) * D);
+    u32x4* dr = (u32x4*)(out + (size_t)r * D);
+    for (int c = l; c < (D >> 3); c += 64) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (from >= 0) v = sr[c];
+        dr[c] = v;
+    }
+}
+
+// Per-row scalars into the compact row space: labels (ignore_index for padding), and up to two
+// fp32 vectors (0 for padding).
+__global__ __launch_bounds__(256) void gather_scalars_kernel(const int32_t* __restrict__ perm, int rows_pad,
+        const int32_t* __restrict__ labels, int32_t ignore_index, int32_t* __restrict__ labels_c,
+        const float* __restrict__ a, float* __restrict__ a_c, const float* __restrict__ b, float* __restrict__ b_c) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows_pad) return;
+    const int from = perm[r];
+    labels_c[r] = from >= 0 ? labels[from] : ignore_index;
+    if (a) a_c[r] = from >= 0 ? a[from] : 0.f;
+    if (b) b_c[r] = from >= 0 ? b[from] : 0.f;
+}
+
+// loss / lse of the compact rows back to their original rows.
+__global__ __launch_bounds__(256) void scatter_scalars_kernel(const int32_t* __restrict__ perm, int rows_pad,
+        const float* __restrict__ a_c, float* __restrict__ a, const float* __restrict__ b_c, float* __restrict__ b) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows_pad) return;
+    const int to = perm[r];
+    if (to < 0) return;
+    a[to] = a_c[r];
+    b[to] = b_c[r];
+}
+
+// Zero rows of dHidden for every row that is not valid.  One wavefront per row.
+__global__ __launch_bounds__(256) void zero_invalid_rows_kernel(const int32_t* __restrict__ labels, int N, int V,
+                                                                int32_t ignore_index, int D, uint16_t* __restrict__ out) {
+    const int l = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= N) return;
+    const int32_t y = labels[r];
+    if (y != ignore_index && y >= 0 && y < V) return;
+    u32x4* dr = (u32x4*)(out + (size_t)r * D);
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int c = l; c < (D >> 3); c += 64) dr[c] = z;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -778,12 +896,16 @@ struct Plan {
     int64_t Nb, Vc;             // backward: rows per row block, vocabulary columns per chunk (multiples of 256)
     int gemm_kind;              // backward: output tile of the contractions, 0 = 256 x 256, 1 = 256 x 128
     int split_acc;              // backward: dH running sum as two 16-bit planes (see GemmJob)
+    double model_us;            // modelled time of forward + backward with this plan (ranking only)
     size_t off_status, off_partials, off_sumz, off_dhacc, off_g, total;
+    // row skipping only (budget_rows != 0): compact-row bookkeeping and the staged hidden block
+    int64_t rows_pad;           // compact rows rounded up to 256
+    size_t off_count, off_perm, off_labels_c, off_fa_c, off_fb_c, off_stage;
 };
 
 // Workspace budget: 1 % of the materialised fp32 logits, but never below a floor that
 // keeps the backward chunks large enough to fill the GPU.
-static constexpr size_t kBudgetFloor = 48u << 20;
+static constexpr size_t kBudgetFloor = 48000000;
 
 // Output tiles of the two gradient contractions: 256 x 256, or 256 x 128 with two K groups.
 // The planner picks per shape: the narrow tile costs about 10 % more per flop (more operand
@@ -802,6 +924,7 @@ static GemmTile gemm_tile_of_kind(int kind) {
 static int g_force_row_tiles = 0, g_force_vocab_tiles = 0;
 static int g_force_gemm_cols = 0;        // cce_set_backward_gemm_tile: 0 = automatic, 128 or 256
 static int g_force_split_acc = 0;        // cce_set_backward_accumulator: 0 = automatic, 1 = fp32, 2 = split
+static int g_force_row_skipping = 0;     // cce_set_row_skipping: 0 = automatic, 1 = never, 2 = whenever rows can be skipped
 
 // Rough time model of the backward pipeline, in microseconds, used only to rank tilings.
 // One compute unit runs one workgroup at a time.  Measured on MI355X with random bf16 data:
@@ -854,12 +977,16 @@ struct BackwardModel {
     }
 };
 
-static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
+// budget_rows != 0 selects row skipping: the plan is made for N compact rows while the workspace
+// budget (1 % of the materialised logits) is that of the budget_rows original rows, and the
+// workspace also holds the compact-row bookkeeping and one staged block of hidden rows.
+static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_rows = 0) {
     if (N <= 0 || D <= 0 || V <= 0) return false;
-    struct Key { int64_t N, D, V; int fa, fb, fc, fs; Plan plan; bool valid; };
-    static thread_local Key cache = {0, 0, 0, 0, 0, 0, 0, {}, false};
-    if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.fa == g_force_row_tiles &&
+    struct Key { int64_t N, D, V, B; int fa, fb, fc, fs; Plan plan; bool valid; };
+    static thread_local Key cache = {0, 0, 0, 0, 0, 0, 0, 0, {}, false};
+    if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.B == budget_rows && cache.fa == g_force_row_tiles &&
         cache.fb == g_force_vocab_tiles && cache.fc == g_force_gemm_cols && cache.fs == g_force_split_acc) { *p = cache.plan; return true; }
+    const bool compact = budget_rows != 0;
 
     const int cus = device_cu_count();
     const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
@@ -883,14 +1010,16 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     // per (token, split): (max, sum-exp) pair + the logit sum that label smoothing needs
     const size_t md_bytes = (size_t)round_up((int64_t)N * S * 8, 256);
     const size_t partial_bytes = md_bytes + (size_t)round_up((int64_t)N * S * 4, 256);
-    size_t budget = (size_t)((double)N * (double)V * 4.0 * 0.01);
+    size_t budget = (size_t)((double)(compact ? budget_rows : N) * (double)V * 4.0 * 0.01);
     if (budget < kBudgetFloor) budget = kBudgetFloor;
-    const size_t fixed = 256 + partial_bytes;
+    const size_t scalar_bytes = compact ? (size_t)round_up(Np * 4, 256) : 0;      // one per-row int32 / fp32 array
+    const size_t fixed = 256 + partial_bytes + (compact ? 256 + 4 * scalar_bytes : 0);
 
     // Row block of a tiles, vocabulary chunk of b tiles.
     int acc_bytes = 4;          // per element of the dH running sum: 4 (fp32) or 2 (split planes)
     auto bytes_needed = [&](int64_t a, int64_t b) {
-        return (double)fixed + (double)round_up(a * 256 * D * acc_bytes, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
+        return (double)fixed + (double)round_up(a * 256 * D * acc_bytes, 256) + (double)(a * 256) * (double)(b * 256) * 2.0 +
+               (compact ? (double)(a * 256 * D * 2) : 0.0);
     };
     // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
     auto plan_for_kind = [&](int kind, int* a_out, int* b_out) -> double {
@@ -950,6 +1079,11 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
         best_a = sa; best_b = sb; best_kind = skind; p->split_acc = 1;
     }
     acc_bytes = p->split_acc ? 2 : 4;
+    {
+        BackwardModel fm{cus, D, gemm_tile_of_kind(0)};
+        const int64_t rounds = ((int64_t)p->TT * p->S + cus - 1) / cus;
+        p->model_us = (p->split_acc ? cost_split : cost_f32) + (double)(rounds * ((p->VT + p->S - 1) / p->S)) * fm.t_tile();
+    }
     p->gemm_kind = best_kind;
     p->Nb = (int64_t)best_a * 256;
     p->Vc = (int64_t)best_b * 256;
@@ -961,7 +1095,18 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p) {
     p->off_dhacc = p->off_partials + partial_bytes;
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * (p->split_acc ? 2 : 4), 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
-    cache = {N, D, V, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, g_force_split_acc, *p, true};
+    p->rows_pad = Np;
+    p->off_count = p->off_perm = p->off_labels_c = p->off_fa_c = p->off_fb_c = p->off_stage = 0;
+    if (compact) {
+        p->off_stage = round_up((int64_t)p->total, 256);
+        p->off_count = p->off_stage + (size_t)(p->Nb * D * 2);
+        p->off_perm = p->off_count + 256;
+        p->off_labels_c = p->off_perm + scalar_bytes;
+        p->off_fa_c = p->off_labels_c + scalar_bytes;
+        p->off_fb_c = p->off_fa_c + scalar_bytes;
+        p->total = p->off_fb_c + scalar_bytes;
+    }
+    cache = {N, D, V, budget_rows, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, g_force_split_acc, *p, true};
     return true;
 }
 
@@ -999,10 +1144,14 @@ static bool ensure_kernel_attributes() {
     if (!allow_big_lds(lse_partial_kernel<false, true>, TileBig::kLdsBytes)) return false;
     if (!allow_big_lds(grad_tile_kernel<false>, kGradTileLds)) return false;
     if (!allow_big_lds(grad_tile_kernel<true>, kGradTileLds)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig, false>, kGemmLdsBig)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, false>, kGemmLdsNarrow)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig, true>, kGemmLdsBig)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, true>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 0>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 0>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 1>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 1>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 2>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 2>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 3>, kGemmLdsBig)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 3>, kGemmLdsNarrow)) return false;
     done[dev] = true;
     return true;
 }
@@ -1043,6 +1192,14 @@ static bool variant_ok(float label_smoothing, float z_loss) {
     return label_smoothing >= 0.f && label_smoothing < 1.f && z_loss >= 0.f && isfinite(z_loss);
 }
 
+// Row skipping: what the two implementation functions need to run in the compact row space.
+struct CompactCtx {
+    Plan plan;                  // made for the compact rows
+    const int32_t* perm;        // device: original row of each compact row, -1 for padding
+    const void* hidden_full;    // backward: the caller's hidden [N, D]; rows are staged per row block
+    uint16_t* stage;            // backward: staging of one block of gathered hidden rows
+};
+
 // Forward over the V rows of `weight`, which are the rows [v_off, v_off + V) of the full
 // matrix.  With `stats` the per-token shard statistics are written instead of loss / lse
 // (`smooth` then says whether the logit sums are wanted).
@@ -1051,7 +1208,7 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
                         float label_smoothing, float z_loss,
                         float* loss, float* lse, float* mean_loss,
                         int64_t v_off, float* stats, bool want_sumz, const Fp8Scales* fp8_in,
-                        void* workspace, size_t workspace_bytes, void* stream_) {
+                        void* workspace, size_t workspace_bytes, void* stream_, const CompactCtx* cc = nullptr) {
     Plan p;
     Fp8Scales fp8 = {nullptr, nullptr, 0, 0};
     if (fp8_in) {
@@ -1064,8 +1221,12 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
     if ((uintptr_t)stats & 15) return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     if (v_off < 0 || v_off > (1 << 30)) return CCE_ERR_INVALID;
-    int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
-    if (rc != CCE_OK) return rc;
+    if (cc) {
+        p = cc->plan;           // arguments were checked, the status word cleared, by the caller
+    } else {
+        int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
+        if (rc != CCE_OK) return rc;
+    }
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
     int32_t* status = (int32_t*)(ws + p.off_status);
@@ -1073,24 +1234,25 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
     const bool smooth = stats ? want_sumz : label_smoothing != 0.f;
     float* sumz = smooth ? (float*)(ws + p.off_sumz) : (float*)nullptr;
 
+    const int32_t* fwd_perm = cc ? cc->perm : (const int32_t*)nullptr;
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    if (!cc) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     {
         ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
         if (fp8_in)
             hipLaunchKernelGGL((lse_partial_kernel<false, true>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8, fwd_perm);
         else if (smooth)
             hipLaunchKernelGGL((lse_partial_kernel<true, false>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8, fwd_perm);
         else
             hipLaunchKernelGGL((lse_partial_kernel<false, false>), dim3(p.TT * p.S), dim3(kThreads), TileBig::kLdsBytes, stream,
-                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8);
+                               hidden, weight, (int)N, (int)D, (int)V, p.TT, p.VT, p.S, partials, sumz, fp8, fwd_perm);
     }
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
                        (const uint16_t*)hidden, (const uint16_t*)weight, labels, partials, (const float*)sumz,
                        (int)N, (int)D, (int)V, p.S, ignore_index, label_smoothing, z_loss, loss, lse, status,
-                       (int)v_off, (float4*)stats, fp8);
+                       (int)v_off, (float4*)stats, fp8, fwd_perm);
     if (mean_loss && !stats)
         hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
                            (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss);
@@ -1149,7 +1311,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
                          float label_smoothing, float z_loss,
                          void* dHidden, float* dW, int accumulate_dW,
                          const void* logit_hidden, const void* logit_weight, const Fp8Scales* fp8_in,
-                         void* workspace, size_t workspace_bytes, void* stream_) {
+                         void* workspace, size_t workspace_bytes, void* stream_, const CompactCtx* cc = nullptr) {
     Plan p;
     // The logit tiles are recomputed from logit_hidden / logit_weight (the bf16 operands, or
     // their E4M3 copies with fp8_in); the two gradient contractions always use the bf16 ones.
@@ -1165,8 +1327,12 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
     if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     if (v_off < 0 || V_total > (1 << 30) || v_off + V > V_total) return CCE_ERR_INVALID;
-    int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
-    if (rc != CCE_OK) return rc;
+    if (cc) {
+        p = cc->plan;
+    } else {
+        int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
+        if (rc != CCE_OK) return rc;
+    }
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
@@ -1200,6 +1366,16 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
     for (int k = 0; k < K; ++k) {
         const Step& st = steps[k];
         const int ldg = st.v_tiles * 256;                       // the chunk is stored densely padded
+        if (cc && st.first_chunk) {
+            // row skipping: the hidden rows of this block of compact rows are gathered once into the
+            // staging area; `hidden` below then points r0 rows in front of it, so that the kernels'
+            // row indices r0 .. r0 + rows - 1 (all they touch of it within this block) land inside
+            hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((st.rows + 3) / 4)), dim3(256), 0, stream,
+                               (const uint16_t*)cc->hidden_full, cc->perm, (int)st.r0, (int)st.rows, (int)D, cc->stage);
+            hidden = (const void*)(cc->stage - (ptrdiff_t)st.r0 * D);
+        }
+        // rows of `hidden` the gradient tile kernel may touch: up to the end of this block when staged
+        const int n_rows_h = cc ? (int)(st.r0 + st.rows) : (int)N;
         // 1. gradient tiles of this [row block x chunk]
         {
             ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
@@ -1211,7 +1387,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
             else
                 hipLaunchKernelGGL(grad_tile_kernel<false>, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
                                    hidden, weight, labels, lse, dloss, (const float*)mean_scale,
-                                   (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
+                                   n_rows_h, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
                                    (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8);
         }
         // 2. both contractions in one launch
@@ -1223,8 +1399,9 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dh.k_total = ldg; dh.n_tiles = d_tiles; dh.n_work = st.row_tiles * per256 * d_tiles;
         dh.m_valid = (int)st.rows; dh.n_valid = (int)D;
         dh.out_f32 = p.split_acc ? (float*)nullptr : (float*)(ws + p.off_dhacc); dh.ld_out = D; dh.beta = st.first_chunk ? 0 : 1;
-        dh.out_hi = (uint16_t*)dHidden + (size_t)st.r0 * D; dh.out_lo = p.split_acc ? dh_lo : (uint16_t*)nullptr;
+        dh.out_hi = (uint16_t*)dHidden + (cc ? (size_t)0 : (size_t)st.r0 * D); dh.out_lo = p.split_acc ? dh_lo : (uint16_t*)nullptr;
         dh.final = st.last_chunk ? 1 : 0;
+        dh.row_map = cc ? cc->perm + st.r0 : (const int32_t*)nullptr;
         // dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
         GemmJob dw;
         dw.a_kmajor = 0;
@@ -1233,7 +1410,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dw.k_total = st.row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = st.v_tiles * per256 * d_tiles;
         dw.m_valid = (int)st.cols; dw.n_valid = (int)D;
         dw.out_f32 = dW + (size_t)st.v0 * D; dw.ld_out = D; dw.beta = (st.r0 > 0 || accumulate_dW) ? 1 : 0;
-        dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0;
+        dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0; dw.row_map = nullptr;
         const bool dh_first = dh.k_total >= dw.k_total;          // longer reduction first
         const GemmJob& first = dh_first ? dh : dw;
         const GemmJob& second = dh_first ? dw : dh;
@@ -1241,14 +1418,17 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
 
         {
             ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
-            if (gt.kind == 0 && !p.split_acc)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileBig, false>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
-            else if (gt.kind == 0)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileBig, true>), dim3(work), dim3(kThreads), kGemmLdsBig, stream, first, second);
-            else if (!p.split_acc)
-                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow, false>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
-            else
-                hipLaunchKernelGGL((grad_gemm_kernel<TileNarrow, true>), dim3(work), dim3(kThreads), kGemmLdsNarrow, stream, first, second);
+            const int mode = (p.split_acc ? 1 : 0) | (cc ? 2 : 0);
+#define CCE_LAUNCH_GEMM(CFG, MODE, LDS) \
+    hipLaunchKernelGGL((grad_gemm_kernel<CFG, MODE>), dim3(work), dim3(kThreads), LDS, stream, first, second)
+            if (gt.kind == 0) {
+                if (mode == 0) CCE_LAUNCH_GEMM(TileBig, 0, kGemmLdsBig); else if (mode == 1) CCE_LAUNCH_GEMM(TileBig, 1, kGemmLdsBig);
+                else if (mode == 2) CCE_LAUNCH_GEMM(TileBig, 2, kGemmLdsBig); else CCE_LAUNCH_GEMM(TileBig, 3, kGemmLdsBig);
+            } else {
+                if (mode == 0) CCE_LAUNCH_GEMM(TileNarrow, 0, kGemmLdsNarrow); else if (mode == 1) CCE_LAUNCH_GEMM(TileNarrow, 1, kGemmLdsNarrow);
+                else if (mode == 2) CCE_LAUNCH_GEMM(TileNarrow, 2, kGemmLdsNarrow); else CCE_LAUNCH_GEMM(TileNarrow, 3, kGemmLdsNarrow);
+            }
+#undef CCE_LAUNCH_GEMM
         }
     }
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
@@ -1264,6 +1444,133 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
     return backward_impl(hidden, weight, labels, lse, dloss, grad_scale, N, D, V, 0, V, ignore_index,
                          label_smoothing, z_loss, dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr,
                          workspace, workspace_bytes, stream_);
+}
+
+// Row skipping pays when enough rows can be skipped: the compact row space costs a label scan, a
+// copy of the hidden rows, and part of the workspace (one staged row block), and its tiling may
+// fit the launches worse.  The plan for the compact rows is used when the time model rates it
+// at least 2 % faster than the plan for all rows (plus ~30 us for the extra small kernels);
+// otherwise every row is processed, exactly as cce_forward / cce_backward do.
+static bool choose_compact_plan(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows, Plan* p, bool* use_compact) {
+    Plan plain, comp;
+    int64_t M = max_valid_rows < N ? max_valid_rows : N;
+    if (M < 1) M = 1;
+    if (!make_plan(N, D, V, &plain)) return false;
+    *use_compact = false;
+    *p = plain;
+    if (M < N && g_force_row_skipping != 1 && make_plan(M, D, V, &comp, N) &&
+        (g_force_row_skipping == 2 || comp.model_us + 30.0 < 0.98 * plain.model_us)) {
+        *use_compact = true;
+        *p = comp;
+    }
+    return true;
+}
+
+// Row skipping: shared argument checks and plan.
+static int compact_plan(const void* hidden, const void* weight, const int32_t* labels, int64_t N, int64_t D, int64_t V,
+                        int64_t max_valid_rows, void* workspace, size_t workspace_bytes, Plan* p, bool* compact_out) {
+    if (!hidden || !weight || !labels || !workspace) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || V <= 0 || max_valid_rows < 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (N > (1 << 30) || V > (1 << 30) || V * D * 2 >= ((int64_t)1 << 32) || N * D * 2 >= ((int64_t)1 << 32))
+        return CCE_ERR_UNSUPPORTED;
+    if (((uintptr_t)hidden | (uintptr_t)weight | (uintptr_t)labels) & 15) return CCE_ERR_INVALID;
+    if ((uintptr_t)workspace & 255) return CCE_ERR_INVALID;
+    bool use_compact = false;
+    if (!choose_compact_plan(N, D, V, max_valid_rows, p, &use_compact)) return CCE_ERR_INVALID;
+    if (workspace_bytes < p->total) return CCE_ERR_INVALID;
+    *compact_out = use_compact;
+    return CCE_OK;
+}
+
+int cce_set_row_skipping(int mode) {
+    if (mode < 0 || mode > 2) return CCE_ERR_INVALID;
+    g_force_row_skipping = mode;
+    return CCE_OK;
+}
+
+int cce_get_row_skipping(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows, int* skipping) {
+    Plan p;
+    bool use_compact = false;
+    if (!skipping || N <= 0 || D <= 0 || V <= 0 || max_valid_rows < 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (!choose_compact_plan(N, D, V, max_valid_rows, &p, &use_compact)) return CCE_ERR_INVALID;
+    *skipping = use_compact ? 1 : 0;
+    return CCE_OK;
+}
+
+size_t cce_compact_workspace_bytes(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows) {
+    Plan p;
+    bool use_compact = false;
+    if (N <= 0 || D <= 0 || V <= 0 || D % 64 != 0 || max_valid_rows < 0) return 0;
+    if (!choose_compact_plan(N, D, V, max_valid_rows, &p, &use_compact)) return 0;
+    return p.total;
+}
+
+int cce_forward_compact(const void* hidden, const void* weight, const int32_t* labels,
+                        int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                        float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+    CompactCtx cc;
+    if (!loss || !lse || (((uintptr_t)loss | (uintptr_t)lse) & 3)) return CCE_ERR_INVALID;
+    bool use_compact = false;
+    int rc = compact_plan(hidden, weight, labels, N, D, V, max_valid_rows, workspace, workspace_bytes, &cc.plan, &use_compact);
+    if (rc != CCE_OK) return rc;
+    if (!use_compact)
+        return forward_impl(hidden, weight, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+                            0, nullptr, false, nullptr, workspace, workspace_bytes, stream_);
+    if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
+    const Plan& p = cc.plan;
+    const int64_t M = max_valid_rows < 1 ? 1 : (max_valid_rows < N ? max_valid_rows : N);
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)workspace;
+    int32_t* status = (int32_t*)(ws + p.off_status);
+    int32_t* perm = (int32_t*)(ws + p.off_perm);
+    const int rows_pad = (int)p.rows_pad;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
+                       (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status, loss, lse);
+    // the kernels fetch hidden rows through perm and write loss / lse to the original rows
+    cc.perm = perm; cc.hidden_full = hidden; cc.stage = nullptr;
+    return forward_impl(hidden, weight, labels, M, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+                        0, nullptr, false, nullptr, workspace, workspace_bytes, stream_, &cc);
+}
+
+int cce_backward_compact(const void* hidden, const void* weight, const int32_t* labels,
+                         const float* lse, const float* dloss,
+                         int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                         void* dHidden, float* dW, int accumulate_dW,
+                         void* workspace, size_t workspace_bytes, void* stream_) {
+    CompactCtx cc;
+    if (!lse || !dloss || !dHidden || !dW) return CCE_ERR_INVALID;
+    if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
+    bool use_compact = false;
+    int rc = compact_plan(hidden, weight, labels, N, D, V, max_valid_rows, workspace, workspace_bytes, &cc.plan, &use_compact);
+    if (rc != CCE_OK) return rc;
+    if (!use_compact)
+        return backward_impl(hidden, weight, labels, lse, dloss, 1.f, N, D, V, 0, V, ignore_index, 0.f, 0.f,
+                             dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_);
+    if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
+    const Plan& p = cc.plan;
+    const int64_t M = max_valid_rows < 1 ? 1 : (max_valid_rows < N ? max_valid_rows : N);
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)workspace;
+    int32_t* status = (int32_t*)(ws + p.off_status);
+    int32_t* perm = (int32_t*)(ws + p.off_perm);
+    int32_t* labels_c = (int32_t*)(ws + p.off_labels_c);
+    float* lse_c = (float*)(ws + p.off_fa_c);
+    float* dloss_c = (float*)(ws + p.off_fb_c);
+    const int rows_pad = (int)p.rows_pad;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
+                       (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status,
+                       (float*)nullptr, (float*)nullptr);
+    hipLaunchKernelGGL(gather_scalars_kernel, dim3((unsigned)((rows_pad + 255) / 256)), dim3(256), 0, stream,
+                       (const int32_t*)perm, rows_pad, labels, ignore_index, labels_c, lse, lse_c, dloss, dloss_c);
+    hipLaunchKernelGGL(zero_invalid_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
+                       labels, (int)N, (int)V, ignore_index, (int)D, (uint16_t*)dHidden);
+    cc.perm = perm; cc.hidden_full = hidden; cc.stage = (uint16_t*)(ws + p.off_stage);
+    return backward_impl(hidden, weight, labels_c, lse_c, dloss_c, 1.f, M, D, V, 0, V, ignore_index, 0.f, 0.f,
+                         dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_, &cc);
 }
 
 int cce_fp8_forward(const void* hidden_q, const void* hidden_scales, const void* weight_q, const void* weight_scales,

@@ -102,7 +102,10 @@ struct OperandTile {
 
     // free0: first free index of the tile; free_n: number of valid free indices in the matrix
     // (a multiple of 8, at least 8, for a K-slow operand); k_n: valid K extent.
-    __device__ __forceinline__ void init(const void* p, int64_t ld, int free0, int free_n, int k_n) {
+    // row_map (K-major operands only): free index f is fetched from matrix row row_map[f] (row 0
+    // where the map holds -1; such rows are padding whose products the caller discards).
+    __device__ __forceinline__ void init(const void* p, int64_t ld, int free0, int free_n, int k_n,
+                                         const int32_t* row_map = nullptr) {
         base = (const char*)p;
         ld_bytes = (uint32_t)(ld * 2);
         k_last = k_n - 1;
@@ -114,6 +117,10 @@ struct OperandTile {
             for (int i = 0; i < NL; ++i) {
                 int row = free0 + 64 * i + 8 * wave + (lane >> 3);
                 row = row < free_n ? row : free_n - 1;
+                if (row_map) {
+                    const int mapped = row_map[row];
+                    row = mapped < 0 ? 0 : mapped;
+                }
                 off[i] = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
                 krow[i] = 0;
             }

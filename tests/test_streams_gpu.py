@@ -93,12 +93,20 @@ def _shard_step(B, b, stream=None):
                          d_hidden=b["dH"], d_weight=b["dW"][lo:hi], stream=stream)
 
 
-@pytest.mark.parametrize("which", ["fp8", "shard"])
+def _compact_step(B, b, stream=None):
+    B.cce_forward_compact(b["H"], b["W"], b["y"], b["n_valid"], IGN, workspace=b["wc"], loss=b["loss"], lse=b["lse"],
+                          stream=stream)
+    B.cce_backward_compact(b["H"], b["W"], b["y"], b["lse"], b["dl"], b["n_valid"], IGN, workspace=b["wc"],
+                           d_hidden=b["dH"], d_weight=b["dW"], stream=stream)
+
+
+@pytest.mark.parametrize("which", ["fp8", "shard", "compact"])
 def test_graph_capture_of_the_variants(B, which):
     """The FP8 and the vocabulary-shard entry points are launches only as well: captured,
     replayed three times with eager work in between, every replay equal to the eager result."""
     w = I.make_workload(I.custom_spec(520, 256, 2100, seed=43, ignore_frac=0.1))
-    step = _fp8_step if which == "fp8" else _shard_step
+    step = {"fp8": _fp8_step, "shard": _shard_step, "compact": _compact_step}[which]
+    B.set_row_skipping(2 if which == "compact" else 0)
     def buffers():
         b = _buffers(B, w)
         N, D = w.hidden.shape
@@ -108,6 +116,8 @@ def test_graph_capture_of_the_variants(B, which):
         b["hs"] = torch.empty(B.fp8_scale_bytes(N, D), dtype=torch.uint8, device="cuda")
         b["wsc"] = torch.empty(B.fp8_scale_bytes(V, D), dtype=torch.uint8, device="cuda")
         b["stats"] = torch.empty(2, N, 4, device="cuda")
+        b["n_valid"] = w.n_valid
+        b["wc"] = B.alloc_compact_workspace(N, D, V, w.n_valid)
         b["dW"].zero_()
         return b
     ref, b = buffers(), buffers()
@@ -129,3 +139,4 @@ def test_graph_capture_of_the_variants(B, which):
         for k in ("loss", "lse", "dH", "dW"):
             assert torch.equal(ref[k], b[k]), (which, rep, k)
         assert float(junk) == float(junk)
+    B.set_row_skipping(0)
