@@ -1041,8 +1041,11 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
                 auto block_cost = [&](int aa, bool beta) {
                     return (nch - 1) * model.step(aa, b, beta) + model.step(aa, b_last, beta);
                 };
-                const double cost = (nblk == 1) ? block_cost(a_last, false)
-                                                : block_cost(a, false) + (nblk - 2) * block_cost(a, true) + block_cost(a_last, true);
+                double cost = (nblk == 1) ? block_cost(a_last, false)
+                                          : block_cost(a, false) + (nblk - 2) * block_cost(a, true) + block_cost(a_last, true);
+                // measured per contraction launch: the split running sum costs 2 us, 9 us when its
+                // upper-half plane is also reached through the row map of the compact row space
+                if (acc_bytes == 2) cost += (double)nblk * nch * (compact ? 9.0 : 2.0);
                 if (cost < best_cost) { best_cost = cost; *a_out = a; *b_out = b; }
             }
         }
