@@ -46,6 +46,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="qwen05b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-rows", action="store_true",
+                    help="time cce_forward + cce_backward (every row goes through the kernels) as the headline "
+                         "instead of the row-skipping entry points")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference that scales the "
@@ -81,9 +84,24 @@ def main() -> int:
     dH = torch.empty(N, D, dtype=torch.bfloat16, device=dev)
     dW = torch.empty(V, D, dtype=torch.float32, device=dev)
 
-    def step():
+    def all_rows_step():
         B.cce_forward(H, W, y, w.spec.ignore_index, workspace=ws, loss=loss, lse=lse)
         B.cce_backward(H, W, y, lse, dl, w.spec.ignore_index, workspace=ws, d_hidden=dH, d_weight=dW)
+
+    # Row skipping (include/cce_compact.h): rows whose label is ignore_index take no part in the
+    # loss, so the entry points that are told how many rows are valid leave them out of every
+    # product.  The count comes from the host copy of the labels, as a data loader has it.
+    n_valid_host = int(((w.labels != w.spec.ignore_index) & (w.labels >= 0) & (w.labels < V)).sum())
+    skipping = (not args.all_rows) and B.get_row_skipping(N, D, V, n_valid_host)
+    wc = B.alloc_compact_workspace(N, D, V, n_valid_host)
+
+    def skip_step():
+        B.cce_forward_compact(H, W, y, n_valid_host, w.spec.ignore_index, workspace=wc, loss=loss, lse=lse)
+        B.cce_backward_compact(H, W, y, lse, dl, n_valid_host, w.spec.ignore_index, workspace=wc, d_hidden=dH, d_weight=dW)
+
+    step = skip_step if skipping else all_rows_step
+    ws_used = wc if skipping else ws
+    rows_run = n_valid_host if skipping else N          # rows whose products are computed
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -124,10 +142,11 @@ def main() -> int:
     n_valid = w.n_valid
     mean_loss = float(loss.sum().item()) / max(n_valid, 1)
     grad_norm = float(dW.double().pow(2).sum().sqrt().item())
-    assert np.isfinite(mean_loss) and grad_norm > 0.0 and B.read_status(ws) == 0
+    assert np.isfinite(mean_loss) and grad_norm > 0.0 and B.read_status(ws_used) == 0
 
-    nvd = float(N) * V * D
-    # algorithmic MFMA flops per step of each family (all N rows are processed)
+    nvd = float(rows_run) * V * D
+    # algorithmic MFMA flops per step of each family, over the rows that are computed (all N, or
+    # the valid ones when rows are skipped: flops that are not run are not counted)
     fam_flops = {"lse_partial_kernel": 2 * nvd, "grad_tile_kernel": 2 * nvd, "grad_gemm_kernel": 4 * nvd}
     dom = max(fam, key=lambda k: fam[k][0])
     dom_ms, dom_launches = fam[dom]
@@ -136,7 +155,7 @@ def main() -> int:
     roofline = {
         "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-        "traffic": stored_traffic(args.workload, dom),
+        "traffic": stored_traffic(args.workload, dom + ("/row_skipping" if skipping else "")),
         "avg_launch_us": round(dom_ms * 1e3 / max(dom_launches, 1), 2),
         "launches_per_step": dom_launches // max(args.steps, 1),
         "flops_per_launch": fam_flops[dom] * args.steps / max(dom_launches, 1),
@@ -201,20 +220,18 @@ def main() -> int:
                "backward_us": round(b_us, 1)}
         del hq, hsc, wq, wsc
 
-    # Row skipping (include/cce_compact.h): the same step through the entry points that take the
-    # number of valid rows from the host (counted here from the host copy of the labels, as a
-    # data loader would) and leave the ignored rows out of every product.  Not `value`.
-    n_valid_host = int(((w.labels != w.spec.ignore_index) & (w.labels >= 0) & (w.labels < V)).sum())
-    wc = B.alloc_compact_workspace(N, D, V, n_valid_host)
-    def compact_step():
-        B.cce_forward_compact(H, W, y, n_valid_host, w.spec.ignore_index, workspace=wc, loss=loss, lse=lse)
-        B.cce_backward_compact(H, W, y, lse, dl, n_valid_host, w.spec.ignore_index, workspace=wc, d_hidden=dH, d_weight=dW)
-    c_us = timed_us(compact_step, reps=10)
-    skip = {"rows_skipped": bool(B.get_row_skipping(N, D, V, n_valid_host)), "valid_rows": n_valid_host,
-            "ms_per_step": round(c_us * 1e-3, 4), "tokens_per_s": round(N / (c_us * 1e-6), 1),
-            "tflops_executed_8NvalidVD": round(8.0 * n_valid_host * V * D / (c_us * 1e-6) / 1e12, 1),
-            "workspace_bytes": int(wc.numel())}
-    del wc
+    # The other path of the two (all rows / row skipping), same buffers, for comparison.
+    other = all_rows_step if skipping else skip_step
+    o_us = timed_us(other, reps=10)
+    o_rows = N if skipping else n_valid_host
+    other_path = {"entry_points": "cce_forward + cce_backward (all rows)" if skipping
+                  else "cce_forward_compact + cce_backward_compact", 
+                  "rows_skipped": (not skipping) and bool(B.get_row_skipping(N, D, V, n_valid_host)),
+                  "ms_per_step": round(o_us * 1e-3, 4), "tokens_per_s": round(N / (o_us * 1e-6), 1),
+                  "rows_computed": int(o_rows),
+                  "tflops_executed": round(8.0 * o_rows * V * D / (o_us * 1e-6) / 1e12, 1),
+                  "pct_bf16_mfma_peak": round(100 * 8.0 * o_rows * V * D / (o_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+                  "workspace_bytes": int((ws if skipping else wc).numel())}
 
     # what the peak is divided by: the nominal figure, the one the device properties give
     # (compute units x 4096 flop/clock x clock), and a register-only MFMA loop on this device
@@ -250,16 +267,20 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={N} D={D} V={V}, {w.spec.ignore_frac:.0%} ignore_index, "
-                               f"seed {w.spec.seed}", "n_valid": n_valid},
+                               f"seed {w.spec.seed}", "n_valid": n_valid,
+                   "entry_points": "cce_forward_compact + cce_backward_compact (rows with ignore_index are left out of "
+                                   "every product; the count of valid rows is taken from the host copy of the labels)"
+                                   if skipping else "cce_forward + cce_backward (all rows)"},
         "valid_tokens_per_s": round(n_valid / (ms_per_step * 1e-3), 1),
         "tflops_executed_8NVD": round(executed_tflops, 1),
         "tflops_model_6NVD": round(6 * nvd / (ms_per_step * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100 * executed_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
-        "workspace_bytes": int(ws.numel()),
-        "workspace_pct_of_logits": round(100.0 * ws.numel() / B.materialised_logit_bytes(N, V), 3),
+        "rows_computed": int(rows_run),
+        "workspace_bytes": int(ws_used.numel()),
+        "workspace_pct_of_logits": round(100.0 * ws_used.numel() / B.materialised_logit_bytes(N, V), 3),
         "backward_tiling_256": list(B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
-        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "row_skipping": skip, "mfma_peak": peak_info,
+        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "other_path": other_path, "mfma_peak": peak_info,
     }
     print(json.dumps(out))
     return 0

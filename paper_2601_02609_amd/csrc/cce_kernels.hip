@@ -401,7 +401,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
         const float* __restrict__ lse, const float* __restrict__ dloss, const float* __restrict__ mean_scale,
         int N, int D, int V, int32_t ignore_index, float label_smoothing, float z_loss,
         int row0, int n_row_tiles, int v0, int n_v_tiles,
-        uint16_t* __restrict__ G, int ldg, int v_off, int V_total, const Fp8Scales fp8) {
+        uint16_t* __restrict__ G, int ldg, int v_off, int V_total, const Fp8Scales fp8,
+        const int32_t* __restrict__ perm) {
     typedef TileBig Cfg;
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
     OperandTile<true, Cfg::BN> Bop;
     const int ld = FP8 ? D / 2 : D;               // row length in 2-byte units
     Aop.init(W, ld, vt0, V, ld);
-    Bop.init(H, ld, tok0, N, ld);
+    Bop.init(H, ld, tok0, N, ld, perm);           // perm (row skipping): token t is row perm[t] of H
     if (FP8) {
         ScaleGroup SA, SB;
         const int b_row0 = tok0 + wave_n<Cfg>() * (Cfg::TN * 32);
@@ -550,6 +551,10 @@ constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
 }
 constexpr int kGemmLdsBig = gemm_lds_bytes(TileBig::kLdsBytes, TileBig::BM, TileBig::BN);
 constexpr int kGemmLdsNarrow = gemm_lds_bytes(TileNarrow::kLdsBytes, TileNarrow::BM, TileNarrow::BN);
+// Row skipping: LDS table of the row map of one row block (at most kCompactMaxRowTiles x 256 rows).
+constexpr int kCompactMaxRowTiles = 16;
+constexpr int kRowTableBytes = kCompactMaxRowTiles * 256 * 4;
+static_assert(kGemmLdsNarrow + kRowTableBytes <= 160 * 1024 && kGemmLdsBig + kRowTableBytes <= 160 * 1024, "row table must fit the LDS");
 
 // Output of a job, one of three forms:
 //   fp32 (the dW job): out_f32 (+)= C when `beta`.
@@ -590,6 +595,18 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     OperandTile<false, Cfg::BN> Bop;
     Aop.init(j.A, j.lda, mi * Cfg::BM, j.a_free_n, j.a_k_n);
     Bop.init(j.B, j.ldb, ni * Cfg::BN, j.n_valid, j.b_k_n);
+    if constexpr ((MODE & 2) != 0 && !A_KMAJOR) {
+        // row skipping, dW job: the reduction runs over the compact rows of the block, whose hidden
+        // rows are scattered over the original tensor.  The block's row map is copied into LDS
+        // (behind everything the kernel otherwise uses) and the operand loader looks each of its
+        // k-rows up there.
+        if (j.row_map) {
+            CCE_LDS int32_t* tab = (CCE_LDS int32_t*)(smem + gemm_lds_bytes(Cfg::kLdsBytes, Cfg::BM, Cfg::BN));
+            for (int i = threadIdx.x; i < j.b_k_n; i += kThreads) tab[i] = j.row_map[i];
+            __syncthreads();
+            Bop.kmap = tab;
+        }
+    }
     gemm_mainloop<Cfg, A_KMAJOR, false>(acc, Aop, Bop, j.k_total, smem);
 
     // Epilogue through LDS so that global memory sees 16-byte accesses along full rows:
@@ -730,7 +747,7 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
     const GemmJob& j = in_first ? first : second;
     const int item = in_first ? lin : lin - first.n_work;
     if (j.a_kmajor) run_gemm_job<Cfg, true, MODE>(j, item, smem);
-    else run_gemm_job<Cfg, false, 0>(j, item, smem);
+    else run_gemm_job<Cfg, false, (MODE & 2)>(j, item, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1018,19 +1035,21 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     // Row block of a tiles, vocabulary chunk of b tiles.
     int acc_bytes = 4;          // per element of the dH running sum: 4 (fp32) or 2 (split planes)
     auto bytes_needed = [&](int64_t a, int64_t b) {
-        return (double)fixed + (double)round_up(a * 256 * D * acc_bytes, 256) + (double)(a * 256) * (double)(b * 256) * 2.0 +
-               (compact ? (double)(a * 256 * D * 2) : 0.0);
+        return (double)fixed + (double)round_up(a * 256 * D * acc_bytes, 256) + (double)(a * 256) * (double)(b * 256) * 2.0;
     };
     // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
     auto plan_for_kind = [&](int kind, int* a_out, int* b_out) -> double {
         BackwardModel model{cus, D, gemm_tile_of_kind(kind)};
         if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
             *a_out = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
+            if (compact && *a_out > kCompactMaxRowTiles) *a_out = kCompactMaxRowTiles;
             *b_out = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
             return 0.0;
         }
         double best_cost = 1e300;
-        const int a_max = p->TT < 64 ? p->TT : 64, b_max = p->VT < 128 ? p->VT : 128;
+        // (row skipping: a row block's row map must fit its LDS table)
+        const int a_cap = compact ? kCompactMaxRowTiles : 64;
+        const int a_max = p->TT < a_cap ? p->TT : a_cap, b_max = p->VT < 128 ? p->VT : 128;
         *a_out = 1; *b_out = 1;
         for (int a = 1; a <= a_max; ++a) {
             for (int b = 1; b <= b_max; ++b) {
@@ -1101,8 +1120,8 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     p->rows_pad = Np;
     p->off_count = p->off_perm = p->off_labels_c = p->off_fa_c = p->off_fb_c = p->off_stage = 0;
     if (compact) {
-        p->off_stage = round_up((int64_t)p->total, 256);
-        p->off_count = p->off_stage + (size_t)(p->Nb * D * 2);
+        p->off_stage = 0;
+        p->off_count = round_up((int64_t)p->total, 256);
         p->off_perm = p->off_count + 256;
         p->off_labels_c = p->off_perm + scalar_bytes;
         p->off_fa_c = p->off_labels_c + scalar_bytes;
@@ -1151,10 +1170,10 @@ static bool ensure_kernel_attributes() {
     if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 0>, kGemmLdsNarrow)) return false;
     if (!allow_big_lds(grad_gemm_kernel<TileBig, 1>, kGemmLdsBig)) return false;
     if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 1>, kGemmLdsNarrow)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig, 2>, kGemmLdsBig)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 2>, kGemmLdsNarrow)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileBig, 3>, kGemmLdsBig)) return false;
-    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 3>, kGemmLdsNarrow)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 2>, kGemmLdsBig + kRowTableBytes)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 2>, kGemmLdsNarrow + kRowTableBytes)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileBig, 3>, kGemmLdsBig + kRowTableBytes)) return false;
+    if (!allow_big_lds(grad_gemm_kernel<TileNarrow, 3>, kGemmLdsNarrow + kRowTableBytes)) return false;
     done[dev] = true;
     return true;
 }
@@ -1199,8 +1218,6 @@ static bool variant_ok(float label_smoothing, float z_loss) {
 struct CompactCtx {
     Plan plan;                  // made for the compact rows
     const int32_t* perm;        // device: original row of each compact row, -1 for padding
-    const void* hidden_full;    // backward: the caller's hidden [N, D]; rows are staged per row block
-    uint16_t* stage;            // backward: staging of one block of gathered hidden rows
 };
 
 // Forward over the V rows of `weight`, which are the rows [v_off, v_off + V) of the full
@@ -1369,16 +1386,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
     for (int k = 0; k < K; ++k) {
         const Step& st = steps[k];
         const int ldg = st.v_tiles * 256;                       // the chunk is stored densely padded
-        if (cc && st.first_chunk) {
-            // row skipping: the hidden rows of this block of compact rows are gathered once into the
-            // staging area; `hidden` below then points r0 rows in front of it, so that the kernels'
-            // row indices r0 .. r0 + rows - 1 (all they touch of it within this block) land inside
-            hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((st.rows + 3) / 4)), dim3(256), 0, stream,
-                               (const uint16_t*)cc->hidden_full, cc->perm, (int)st.r0, (int)st.rows, (int)D, cc->stage);
-            hidden = (const void*)(cc->stage - (ptrdiff_t)st.r0 * D);
-        }
-        // rows of `hidden` the gradient tile kernel may touch: up to the end of this block when staged
-        const int n_rows_h = cc ? (int)(st.r0 + st.rows) : (int)N;
+        const int n_rows_h = (int)N;
         // 1. gradient tiles of this [row block x chunk]
         {
             ProfSpan span(CCE_KERNEL_GRAD_TILE, stream);
@@ -1386,12 +1394,14 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
                 hipLaunchKernelGGL(grad_tile_kernel<true>, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
                                    logit_hidden, logit_weight, labels, lse, dloss, (const float*)mean_scale,
                                    (int)N, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
-                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8);
+                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8,
+                                   cc ? cc->perm : (const int32_t*)nullptr);
             else
                 hipLaunchKernelGGL(grad_tile_kernel<false>, dim3(st.row_tiles * st.v_tiles), dim3(kThreads), grad_lds, stream,
                                    hidden, weight, labels, lse, dloss, (const float*)mean_scale,
                                    n_rows_h, (int)D, (int)V, ignore_index, label_smoothing, z_loss,
-                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8);
+                                   (int)st.r0, st.row_tiles, (int)st.v0, st.v_tiles, G, ldg, (int)v_off, (int)V_total, fp8,
+                                   cc ? cc->perm : (const int32_t*)nullptr);
         }
         // 2. both contractions in one launch
         // dH block += G * W_chunk      (M = tokens, K = chunk columns, N = D)
@@ -1409,11 +1419,13 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         GemmJob dw;
         dw.a_kmajor = 0;
         dw.A = G; dw.lda = ldg; dw.a_free_n = ldg; dw.a_k_n = st.row_tiles * 256;
-        dw.B = (const void*)((const uint16_t*)hidden + (size_t)st.r0 * D); dw.ldb = (int)D; dw.b_k_n = (int)st.rows;
+        // (row skipping: hidden is the caller's tensor and the block's rows are reached through the row map)
+        dw.B = cc ? hidden : (const void*)((const uint16_t*)hidden + (size_t)st.r0 * D); dw.ldb = (int)D; dw.b_k_n = (int)st.rows;
         dw.k_total = st.row_tiles * 256; dw.n_tiles = d_tiles; dw.n_work = st.v_tiles * per256 * d_tiles;
         dw.m_valid = (int)st.cols; dw.n_valid = (int)D;
         dw.out_f32 = dW + (size_t)st.v0 * D; dw.ld_out = D; dw.beta = (st.r0 > 0 || accumulate_dW) ? 1 : 0;
-        dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0; dw.row_map = nullptr;
+        dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0;
+        dw.row_map = cc ? cc->perm + st.r0 : (const int32_t*)nullptr;
         const bool dh_first = dh.k_total >= dw.k_total;          // longer reduction first
         const GemmJob& first = dh_first ? dh : dw;
         const GemmJob& second = dh_first ? dw : dh;
@@ -1423,7 +1435,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
             ProfSpan span(CCE_KERNEL_GRAD_GEMM, stream);
             const int mode = (p.split_acc ? 1 : 0) | (cc ? 2 : 0);
 #define CCE_LAUNCH_GEMM(CFG, MODE, LDS) \
-    hipLaunchKernelGGL((grad_gemm_kernel<CFG, MODE>), dim3(work), dim3(kThreads), LDS, stream, first, second)
+    hipLaunchKernelGGL((grad_gemm_kernel<CFG, MODE>), dim3(work), dim3(kThreads), (LDS) + ((MODE) >= 2 ? kRowTableBytes : 0), stream, first, second)
             if (gt.kind == 0) {
                 if (mode == 0) CCE_LAUNCH_GEMM(TileBig, 0, kGemmLdsBig); else if (mode == 1) CCE_LAUNCH_GEMM(TileBig, 1, kGemmLdsBig);
                 else if (mode == 2) CCE_LAUNCH_GEMM(TileBig, 2, kGemmLdsBig); else CCE_LAUNCH_GEMM(TileBig, 3, kGemmLdsBig);
@@ -1533,7 +1545,7 @@ int cce_forward_compact(const void* hidden, const void* weight, const int32_t* l
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
                        (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status, loss, lse);
     // the kernels fetch hidden rows through perm and write loss / lse to the original rows
-    cc.perm = perm; cc.hidden_full = hidden; cc.stage = nullptr;
+    cc.perm = perm;
     return forward_impl(hidden, weight, labels, M, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
                         0, nullptr, false, nullptr, workspace, workspace_bytes, stream_, &cc);
 }
@@ -1571,7 +1583,7 @@ int cce_backward_compact(const void* hidden, const void* weight, const int32_t* 
                        (const int32_t*)perm, rows_pad, labels, ignore_index, labels_c, lse, lse_c, dloss, dloss_c);
     hipLaunchKernelGGL(zero_invalid_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
                        labels, (int)N, (int)V, ignore_index, (int)D, (uint16_t*)dHidden);
-    cc.perm = perm; cc.hidden_full = hidden; cc.stage = (uint16_t*)(ws + p.off_stage);
+    cc.perm = perm;
     return backward_impl(hidden, weight, labels_c, lse_c, dloss_c, 1.f, M, D, V, 0, V, ignore_index, 0.f, 0.f,
                          dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_, &cc);
 }

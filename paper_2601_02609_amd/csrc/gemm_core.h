@@ -99,6 +99,7 @@ struct OperandTile {
     uint32_t off[NL];       // K-major: clamped row offset + swizzled chunk; K-slow: clamped column offset
     int krow[NL];           // K-slow: k-row inside a slice handled by load i
     int k_last;             // K-slow: last valid k (rows beyond are clamped to it)
+    const CCE_LDS int32_t* kmap;   // K-slow, optional: k-row k is matrix row kmap[k] (row 0 where it holds -1)
 
     // free0: first free index of the tile; free_n: number of valid free indices in the matrix
     // (a multiple of 8, at least 8, for a K-slow operand); k_n: valid K extent.
@@ -109,6 +110,7 @@ struct OperandTile {
         base = (const char*)p;
         ld_bytes = (uint32_t)(ld * 2);
         k_last = k_n - 1;
+        kmap = nullptr;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         if (KMAJOR) {
             const int sw = ((lane >> 4) & 3) | ((wave & 1) << 2);
@@ -151,6 +153,10 @@ struct OperandTile {
             } else {
                 int k = k0 + krow[i];
                 k = k < k_last ? k : k_last;
+                if (kmap) {
+                    const int mapped = kmap[k];
+                    k = mapped < 0 ? 0 : mapped;
+                }
                 g = base + (size_t)((uint32_t)k * ld_bytes + off[i]);
             }
             load16_to_lds(g, stage + (wave + 8 * i) * 1024);
