@@ -71,6 +71,31 @@ def test_compact_matches_oracle(B, shape, frac, slack):
     assert e[0] <= LOSS_ATOL and e[1] <= LOSS_ATOL and e[2] <= GRAD_RTOL and e[3] <= GRAD_RTOL
 
 
+@pytest.mark.parametrize("acc", [1, 2])
+@pytest.mark.parametrize("cols", [128, 256])
+def test_compact_with_every_contraction_variant(B, cols, acc):
+    """Row skipping with either contraction tile and either form of the dHidden running sum, over
+    several row blocks and vocabulary chunks (forced tiling), a ragged last block included."""
+    N, D, V = 1500, 512, 2100
+    w = I.make_workload(I.custom_spec(N, D, V, seed=56, ignore_frac=0.3))
+    try:
+        B.set_backward_tiling(2, 3)
+        B.set_backward_gemm_tile(cols)
+        B.set_backward_accumulator(acc)
+        loss, lse, dH, dW, st_f, st_b = run_compact(B, w, w.dloss_var, w.n_valid)
+    finally:
+        B.set_backward_tiling(0, 0)
+        B.set_backward_gemm_tile(0)
+        B.set_backward_accumulator(0)
+    assert st_f == 0 and st_b == 0
+    o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, w.dloss_var, IGN)
+    ign = w.labels == IGN
+    assert np.all(dH[ign] == 0.0)
+    e = (rel_fro(dH, o_dH), rel_fro(dW, o_dW))
+    print(f"[compact] tile 256x{cols} acc {acc}: relF(dH)={e[0]:.2e} relF(dW)={e[1]:.2e}", flush=True)
+    assert e[0] <= GRAD_RTOL and e[1] <= GRAD_RTOL
+
+
 def test_compact_forward_rows_equal_the_plain_forward_bitwise(B):
     """The forward of a row does not depend on which other rows are present: same bits as cce_forward."""
     w = I.make_workload(I.custom_spec(900, 256, 2500, seed=52, ignore_frac=0.3))
