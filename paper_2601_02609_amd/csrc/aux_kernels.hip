@@ -19,7 +19,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned int au32x4;
 typedef __attribute__((ext_vector_type(4))) float af32x4;
 
 constexpr int kNormMaxChunks = 16;      // 16-byte chunks per lane and row: D <= 16 * 64 * 8 = 8192
-constexpr int kNormBackwardBlocks = 512;
+constexpr int kNormBackwardBlocks = 512;        // D <= 1024: four rows in flight per workgroup
+constexpr int kNormBackwardBlocksWide = 1024;   // wider rows: two rows or one
 constexpr int kSumsqBlocks = 1024;
 
 __device__ __forceinline__ void unpack8(const au32x4& p, float (&f)[8]) {
@@ -108,19 +109,29 @@ __global__ __launch_bounds__(256) void rmsnorm_forward_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// RMSNorm backward.  Wavefronts walk the rows with a grid stride; per row
+// RMSNorm backward.  Per row
 //   c = mean_j(dy_j gamma_j xhat_j),  dx_j = rstd (gamma_j dy_j - xhat_j c),  xhat = x rstd,
-// and each lane adds dy_j xhat_j of its columns to a private dgamma partial.  The four
-// wavefronts of a workgroup then add their partials through LDS and the workgroup writes one
-// partial row; dgamma_reduce_kernel sums those rows in a fixed order.
+// and each lane adds dy_j xhat_j of its columns to a private dgamma partial.
+// WPR wavefronts share a row (1 for D <= 1024, 2 up to 2048, 4 beyond): a lane then never
+// holds more than CH = 2 (4 for D > 4096) 16-byte chunks of x and of dy per row, twice (the
+// next row is loaded while this one is processed), which keeps four wavefronts per SIMD
+// resident at every D -- with one wavefront per row, D = 4096 took all 512 registers of a
+// lane and left a single wavefront per SIMD to hide the memory latency.  The wavefronts of a
+// row exchange one partial sum per row through LDS (one barrier per row, slots alternate).
+// The 4 / WPR row groups of a workgroup walk the rows with a grid stride; at the end the
+// groups' dgamma partials are added through LDS and the workgroup writes one partial row;
+// dgamma_reduce_kernel sums those rows in a fixed order.
 // ------------------------------------------------------------------------------------------
-template <int CH>
+template <int CH, int WPR>
 __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
         const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma, const float* __restrict__ rstd_in,
         const uint16_t* __restrict__ dy, int N, int D, uint16_t* __restrict__ dx, float* __restrict__ partials,
         const uint16_t* __restrict__ dres) {
+    constexpr int G = 4 / WPR;                       // rows a workgroup has in flight
     __shared__ float red[4][64 * 8];
+    __shared__ float tsum[2][4];
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int g = w / WPR, wr = w % WPR;
     const int chunks = D >> 3;
     const au32x4* gr = (const au32x4*)gamma;
     float dg[CH][8];
@@ -128,42 +139,55 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
     for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e) dg[i][e] = 0.f;
+    // chunk i of this lane: the wavefronts of a row interleave in units of 64 chunks (1 KB)
+    auto chunk_of = [&](int i) { return l + 64 * (wr + WPR * i); };
 
-    // A row's x and dy are loaded one row ahead of their use (two register sets, A and B),
-    // so that every wavefront always has a row of loads in flight.
     auto load_row = [&](au32x4 (&xv)[CH], au32x4 (&gv)[CH], int row) {
         const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
         const au32x4* dyr = (const au32x4*)(dy + (size_t)row * D);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int c = l + 64 * i;
+            const int c = chunk_of(i);
             if (c < chunks) { xv[i] = xr[c]; gv[i] = dyr[c]; }
         }
     };
-    auto process_row = [&](const au32x4 (&xv)[CH], const au32x4 (&gv)[CH], int row) {
-        au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
-        const float rstd = rstd_in[row];
+    // `live` is false for the row groups that have run out of rows while another group of the
+    // workgroup still has one: they keep taking part in the barrier.
+    auto process_row = [&](const au32x4 (&xv)[CH], const au32x4 (&gv)[CH], int row, bool live, int parity) {
+        const float rstd = live ? rstd_in[row] : 0.f;
         float t = 0.f;
+        if (live) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = l + 64 * i;
-            if (c < chunks) {
-                float xf[8], gf[8], ga[8];
-                unpack8(xv[i], xf);
-                unpack8(gv[i], gf);
-                unpack8(gr[c], ga);
+            for (int i = 0; i < CH; ++i) {
+                const int c = chunk_of(i);
+                if (c < chunks) {
+                    float xf[8], gf[8], ga[8];
+                    unpack8(xv[i], xf);
+                    unpack8(gv[i], gf);
+                    unpack8(gr[c], ga);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xh = xf[e] * rstd;
-                    t = fmaf(gf[e] * ga[e], xh, t);
-                    dg[i][e] = fmaf(gf[e], xh, dg[i][e]);
+                    for (int e = 0; e < 8; ++e) {
+                        const float xh = xf[e] * rstd;
+                        t = fmaf(gf[e] * ga[e], xh, t);
+                        dg[i][e] = fmaf(gf[e], xh, dg[i][e]);
+                    }
                 }
             }
         }
-        const float cmean = wave_sum(t) / (float)D;
+        t = wave_sum(t);
+        if constexpr (WPR > 1) {
+            if (l == 0) tsum[parity][w] = t;
+            __syncthreads();
+            t = 0.f;
+#pragma unroll
+            for (int j = 0; j < WPR; ++j) t += tsum[parity][g * WPR + j];
+        }
+        if (!live) return;
+        const float cmean = t / (float)D;
+        au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int c = l + 64 * i;
+            const int c = chunk_of(i);
             if (c < chunks) {
                 float xf[8], gf[8], ga[8], o[8];
                 unpack8(xv[i], xf);
@@ -181,75 +205,41 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
             }
         }
     };
-    const int stride = gridDim.x * 4;
-    int row = blockIdx.x * 4 + w;
-    if constexpr (CH <= 8) {
-        au32x4 xa[CH], ga_[CH], xb[CH], gb[CH];
-        if (row < N) load_row(xa, ga_, row);
-        while (row < N) {
-            const int r2 = row + stride;
-            if (r2 < N) load_row(xb, gb, r2);
-            process_row(xa, ga_, row);
-            if (r2 >= N) break;
-            const int r3 = r2 + stride;
-            if (r3 < N) load_row(xa, ga_, r3);
-            process_row(xb, gb, r2);
-            row = r3;
-        }
-    } else {
-        // The widest rows (D > 4096) leave no registers to hold a row next to the dgamma
-        // partials: x and dy are read a second time (from L2) for dx.
-        for (; row < N; row += stride) {
-            const au32x4* xr = (const au32x4*)(x + (size_t)row * D);
-            const au32x4* dyr = (const au32x4*)(dy + (size_t)row * D);
-            au32x4* dxr = (au32x4*)(dx + (size_t)row * D);
-            const float rstd = rstd_in[row];
-            float t = 0.f;
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const int c = l + 64 * i;
-                if (c < chunks) {
-                    float xf[8], gf[8], ga[8];
-                    unpack8(xr[c], xf);
-                    unpack8(dyr[c], gf);
-                    unpack8(gr[c], ga);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float xh = xf[e] * rstd;
-                        t = fmaf(gf[e] * ga[e], xh, t);
-                        dg[i][e] = fmaf(gf[e], xh, dg[i][e]);
-                    }
-                }
-            }
-            const float cmean = wave_sum(t) / (float)D;
-            for (int c = l; c < chunks; c += 64) {
-                float xf[8], gf[8], ga[8], o[8];
-                unpack8(xr[c], xf);
-                unpack8(dyr[c], gf);
-                unpack8(gr[c], ga);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = rstd * (ga[e] * gf[e] - xf[e] * rstd * cmean);
-                if (dres) {
-                    float u[8];
-                    unpack8(((const au32x4*)(dres + (size_t)row * D))[c], u);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] += u[e];
-                }
-                dxr[c] = pack8(o);
-            }
-        }
+
+    // Every wavefront of the workgroup makes the same number of trips (that of row group 0);
+    // a row's x and dy are loaded one trip ahead of their use (two register sets, A and B).
+    const int stride = gridDim.x * G;
+    const int first = blockIdx.x * G;
+    const int trips = first < N ? (N - first + stride - 1) / stride : 0;
+    const int row0 = first + g;
+    au32x4 xa[CH], ga_[CH], xb[CH], gb[CH];
+    if (trips > 0 && row0 < N) load_row(xa, ga_, row0);
+    for (int k = 0; k < trips; k += 2) {
+        const int r1 = row0 + k * stride, r2 = r1 + stride, r3 = r2 + stride;
+        if (k + 1 < trips && r2 < N) load_row(xb, gb, r2);
+        process_row(xa, ga_, r1, r1 < N, 0);
+        if (k + 1 >= trips) break;
+        if (k + 2 < trips && r3 < N) load_row(xa, ga_, r3);
+        process_row(xb, gb, r2, r2 < N, 1);
     }
-    // add the four wavefronts' partials, 512 columns (one chunk index i) at a time
+
+    // add the row groups' partials: per chunk index i the workgroup covers 512 * WPR columns
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-        if (64 * i < chunks) {                       // uniform over the workgroup
+        if (64 * WPR * i < chunks) {                 // uniform over the workgroup
 #pragma unroll
             for (int e = 0; e < 8; ++e) red[w][l * 8 + e] = dg[i][e];
             __syncthreads();
 #pragma unroll
-            for (int j = threadIdx.x; j < 512; j += 256) {
-                const int col = 512 * i + j;
-                if (col < D) partials[(size_t)blockIdx.x * D + col] = red[0][j] + red[1][j] + red[2][j] + red[3][j];
+            for (int idx = threadIdx.x; idx < 512 * WPR; idx += 256) {
+                const int wr2 = idx >> 9, j = idx & 511;
+                const int col = 512 * (wr2 + WPR * i) + j;
+                if (col < D) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int gg = 0; gg < G; ++gg) sum += red[gg * WPR + wr2][j];
+                    partials[(size_t)blockIdx.x * D + col] = sum;
+                }
             }
             __syncthreads();
         }
@@ -257,28 +247,32 @@ __global__ __launch_bounds__(256) void rmsnorm_backward_kernel(
 }
 
 // dgamma[col] = sum over the workgroups' partial rows, in a fixed order: a workgroup owns 64
-// columns; its four wavefronts each add every fourth row, then the four sums are added.
-__global__ __launch_bounds__(256) void dgamma_reduce_kernel(const float* __restrict__ partials, int blocks, int D,
-                                                            float* __restrict__ dgamma, int accumulate) {
-    __shared__ float red[4][64];
+// columns; its sixteen wavefronts each add every sixteenth row, eight loads in flight at a
+// time (the sum is a chain of dependent loads otherwise: a handful of workgroups reading a
+// few megabytes is bound by latency, not bandwidth), then the sixteen sums are added.
+__global__ __launch_bounds__(1024) void dgamma_reduce_kernel(const float* __restrict__ partials, int blocks, int D,
+                                                             float* __restrict__ dgamma, int accumulate) {
+    __shared__ float red[16][64];
     const int c = threadIdx.x & 63, r = threadIdx.x >> 6;
     const int col = blockIdx.x * 64 + c;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    float s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = 0.f;
     if (col < D) {
         int b = r;
-        for (; b + 12 < blocks; b += 16) {
-            s0 += partials[(size_t)b * D + col];
-            s1 += partials[(size_t)(b + 4) * D + col];
-            s2 += partials[(size_t)(b + 8) * D + col];
-            s3 += partials[(size_t)(b + 12) * D + col];
+        for (; b + 16 * 7 < blocks; b += 16 * 8) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += partials[(size_t)(b + 16 * e) * D + col];
         }
-        for (; b < blocks; b += 4) s0 += partials[(size_t)b * D + col];
+        for (; b < blocks; b += 16) s[0] += partials[(size_t)b * D + col];
     }
-    red[r][c] = (s0 + s1) + (s2 + s3);
+    red[r][c] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
     __syncthreads();
     if (r == 0 && col < D) {
-        const float s = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
-        dgamma[col] = accumulate ? dgamma[col] + s : s;
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += red[e][c];
+        dgamma[col] = accumulate ? dgamma[col] + t : t;
     }
 }
 
@@ -482,9 +476,15 @@ static bool norm_shape_ok(int64_t N, int64_t D) {
     return N > 0 && D > 0 && D % 64 == 0 && D <= (int64_t)kNormMaxChunks * 512 && N <= ((int64_t)1 << 30);
 }
 
-static int norm_backward_blocks(int64_t N) {
-    const int64_t want = (N + 3) / 4;
-    return (int)(want < kNormBackwardBlocks ? want : kNormBackwardBlocks);
+static int norm_waves_per_row(int64_t D) { return D <= 1024 ? 1 : D <= 2048 ? 2 : 4; }
+
+// Workgroups of the backward: one per 4 / WPR rows until the cap (the partial dgamma rows they
+// write are the workspace, and are read once more by the reduction).
+static int norm_backward_blocks(int64_t N, int64_t D) {
+    const int per = 4 / norm_waves_per_row(D);
+    const int64_t want = (N + per - 1) / per;
+    const int64_t cap = per == 4 ? kNormBackwardBlocks : kNormBackwardBlocksWide;
+    return (int)(want < cap ? want : cap);
 }
 
 }  // namespace cce
@@ -495,7 +495,7 @@ extern "C" {
 
 size_t cce_rmsnorm_workspace_bytes(int64_t N, int64_t D) {
     if (!norm_shape_ok(N, D)) return 0;
-    return (size_t)round_up((int64_t)norm_backward_blocks(N) * D * 4, 256);
+    return (size_t)round_up((int64_t)norm_backward_blocks(N, D) * D * 4, 256);
 }
 
 static int rmsnorm_forward_impl(const void* x, void* residual, const void* gamma, int64_t N, int64_t D, float eps,
@@ -536,14 +536,15 @@ static int rmsnorm_backward_impl(const void* x, const void* gamma, const float* 
     if (((uintptr_t)rstd | (uintptr_t)dgamma) & 3) return CCE_ERR_INVALID;
     if (((uintptr_t)workspace & 255) || workspace_bytes < cce_rmsnorm_workspace_bytes(N, D)) return CCE_ERR_INVALID;
     hipStream_t stream = (hipStream_t)stream_;
-    const int blocks = norm_backward_blocks(N);
+    const int blocks = norm_backward_blocks(N, D);
     float* partials = (float*)workspace;
-#define CCE_NORM_BWD(CH) hipLaunchKernelGGL(rmsnorm_backward_kernel<CH>, dim3(blocks), dim3(256), 0, stream, \
+#define CCE_NORM_BWD(CH, WPR) hipLaunchKernelGGL((rmsnorm_backward_kernel<CH, WPR>), dim3(blocks), dim3(256), 0, stream, \
         (const uint16_t*)x, (const uint16_t*)gamma, rstd, (const uint16_t*)dy, (int)N, (int)D, (uint16_t*)dx, partials, \
         (const uint16_t*)dres)
-    if (D <= 1024) CCE_NORM_BWD(2); else if (D <= 2048) CCE_NORM_BWD(4); else if (D <= 4096) CCE_NORM_BWD(8); else CCE_NORM_BWD(16);
+    if (D <= 1024) CCE_NORM_BWD(2, 1); else if (D <= 2048) CCE_NORM_BWD(2, 2); else if (D <= 4096) CCE_NORM_BWD(2, 4);
+    else CCE_NORM_BWD(4, 4);
 #undef CCE_NORM_BWD
-    hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 63) / 64)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(dgamma_reduce_kernel, dim3((unsigned)((D + 63) / 64)), dim3(1024), 0, stream,
                        (const float*)partials, blocks, (int)D, dgamma, accumulate_dgamma ? 1 : 0);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;

@@ -32,7 +32,10 @@ def _norm_case(N, D, seed):
     return x, gamma, dy
 
 
-@pytest.mark.parametrize("shape", [(1, 64), (7, 896), (1001, 896), (300, 2048), (130, 4096), (5, 8192), (2500, 192)])
+@pytest.mark.parametrize("shape", [(1, 64), (7, 896), (1001, 896), (300, 2048), (130, 4096), (5, 8192), (2500, 192),
+                                   # several trips per workgroup with the row shared by 2 / 4 wavefronts,
+                                   # a last trip only some workgroups (and only some of their rows) take
+                                   (2101, 2048), (4301, 1536), (3000, 3584), (1100, 4096), (2060, 8192)])
 def test_rmsnorm_matches_oracle(B, shape):
     N, D = shape
     eps = 1e-6
@@ -52,7 +55,7 @@ def test_rmsnorm_matches_oracle(B, shape):
     assert np.abs(dgamma.cpu().numpy() - o_dgamma).max() <= 1e-5 * np.abs(o_dgamma).max() + 1e-9
 
 
-@pytest.mark.parametrize("shape", [(3, 64), (1001, 896), (130, 4096), (5, 8192)])
+@pytest.mark.parametrize("shape", [(3, 64), (1001, 896), (130, 4096), (5, 8192), (2101, 2048), (1100, 4096)])
 def test_rmsnorm_residual_form_matches_oracle(B, shape):
     """Fused residual add: the stored residual stream h is the oracle's bf16 sum bit for bit
     (byte work: one rounding of an exact or harmlessly rounded fp32 sum); y, rstd and the
