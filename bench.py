@@ -247,7 +247,7 @@ def main() -> int:
     o_us = timed_us(other, reps=10)
     o_rows = N if skipping else n_valid_host
     other_path = {"entry_points": "cce_forward + cce_backward (all rows)" if skipping
-                  else "cce_forward_compact + cce_backward_compact", 
+                  else "cce_forward_compact + cce_backward_compact",
                   "rows_skipped": (not skipping) and bool(B.get_row_skipping(N, D, V, n_valid_host)),
                   "ms_per_step": round(o_us * 1e-3, 4), "tokens_per_s": round(N / (o_us * 1e-6), 1),
                   "rows_computed": int(o_rows),
@@ -300,7 +300,7 @@ def main() -> int:
         "rows_computed": int(rows_run),
         "workspace_bytes": int(ws_used.numel()),
         "workspace_pct_of_logits": round(100.0 * ws_used.numel() / B.materialised_logit_bytes(N, V), 3),
-        "backward_tiling_256": list(B.get_backward_tiling(N, D, V)),
+        "backward_tiling_256": list(B.get_compact_tiling(N, D, V, n_valid) if skipping else B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
         "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "other_path": other_path, "mfma_peak": peak_info,
     }

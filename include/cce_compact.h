@@ -8,11 +8,11 @@
  * is only known on the device and the tiling of the work is decided on the host, without a
  * synchronisation.  A training loop usually has the labels on the host as well (the data loader
  * produced them): given the count of valid rows -- or any upper bound -- these entry points
- * gather the valid rows, in order, into a compact row space (label scan, then one copy of the
- * hidden rows: all rows in the forward, one row block at a time in the backward), run the
- * unchanged kernels there and scatter loss / lse / dHidden back.  With a fraction f of ignored
- * rows the MFMA work drops by f; the results are those of cce_forward / cce_backward up to fp32
- * summation order (the tiling differs), and exactly equal for ignored rows (zeros).
+ * number the valid rows, in order (one label scan), and run the same kernels in that compact
+ * row space: the operand loaders reach the hidden rows through the row map (nothing is copied),
+ * loss / lse / dHidden go to the original rows.  With a fraction f of ignored rows the MFMA work
+ * drops by f; the results are those of cce_forward / cce_backward up to fp32 summation order
+ * (the tiling differs), and exactly equal for ignored rows (zeros).
  *
  * Conventions are those of cce.h.  A row is valid when its label lies in [0, V) and is not
  * ignore_index.  If there are MORE valid rows than max_valid_rows the surplus rows (the last
@@ -33,10 +33,15 @@ extern "C" {
 #endif
 
 /* Whether the two calls below skip rows for this shape and bound (1) or process all rows like
- * cce_forward / cce_backward (0): skipping costs a label scan, a copy of the hidden rows per row
- * block and part of the workspace, so it is used only where a time model rates it faster (few
- * ignored rows, or a tiling that fits the launches worse, do not pay).  Host only. */
+ * cce_forward / cce_backward (0): skipping costs a label scan and a few small launches, and the
+ * smaller row count may tile the launches worse, so it is used only where a time model rates it
+ * faster (few ignored rows do not pay).  Host only. */
 int cce_get_row_skipping(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows, int* skipping);
+/* The backward tiling cce_backward_compact runs for this shape and bound, in 256-wide tiles per
+ * gradient chunk like cce_get_backward_tiling (which it equals where rows are not skipped).
+ * Host only. */
+int cce_get_compact_tiling(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows,
+                           int* row_tiles, int* vocab_tiles);
 /* Tuning / testing aid: 1 = never skip, 2 = skip whenever max_valid_rows < N, 0 = automatic. */
 int cce_set_row_skipping(int mode);
 

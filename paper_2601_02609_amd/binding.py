@@ -36,7 +36,7 @@ EXPORTED_SYMBOLS = [
     "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
     # include/cce_compact.h
     "cce_compact_workspace_bytes", "cce_forward_compact", "cce_backward_compact",
-    "cce_get_row_skipping", "cce_set_row_skipping",
+    "cce_get_row_skipping", "cce_set_row_skipping", "cce_get_compact_tiling",
     # include/cce_fp8.h
     "cce_fp8_scale_bytes", "cce_quantize_e4m3", "cce_fp8_forward", "cce_fp8_backward",
 ]
@@ -133,6 +133,8 @@ def lib() -> ctypes.CDLL:
                                      vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_get_row_skipping.restype = ctypes.c_int
     L.cce_get_row_skipping.argtypes = [i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int)]
+    L.cce_get_compact_tiling.restype = ctypes.c_int
+    L.cce_get_compact_tiling.argtypes = [i64, i64, i64, i64] + [ctypes.POINTER(ctypes.c_int)] * 2
     L.cce_set_row_skipping.restype = ctypes.c_int
     L.cce_set_row_skipping.argtypes = [ctypes.c_int]
     L.cce_compact_workspace_bytes.restype = sz
@@ -738,6 +740,12 @@ def get_row_skipping(N: int, D: int, V: int, max_valid_rows: int) -> bool:
     m = ctypes.c_int(0)
     _rc(lib().cce_get_row_skipping(N, D, V, max_valid_rows, ctypes.byref(m)), "cce_get_row_skipping")
     return bool(m.value)
+
+
+def get_compact_tiling(N: int, D: int, V: int, max_valid_rows: int) -> Tuple[int, int]:
+    a, b = ctypes.c_int(0), ctypes.c_int(0)
+    _rc(lib().cce_get_compact_tiling(N, D, V, max_valid_rows, ctypes.byref(a), ctypes.byref(b)), "cce_get_compact_tiling")
+    return a.value, b.value
 
 
 def alloc_compact_workspace(N: int, D: int, V: int, max_valid_rows: int, device="cuda") -> torch.Tensor:

@@ -1514,6 +1514,18 @@ int cce_get_row_skipping(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows
     return CCE_OK;
 }
 
+int cce_get_compact_tiling(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows,
+                           int* row_tiles, int* vocab_tiles) {
+    Plan p;
+    bool use_compact = false;
+    if (!row_tiles || !vocab_tiles || N <= 0 || D <= 0 || V <= 0 || max_valid_rows < 0) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    if (!choose_compact_plan(N, D, V, max_valid_rows, &p, &use_compact)) return CCE_ERR_INVALID;
+    *row_tiles = (int)(p.Nb / 256);
+    *vocab_tiles = (int)(p.Vc / 256);
+    return CCE_OK;
+}
+
 size_t cce_compact_workspace_bytes(int64_t N, int64_t D, int64_t V, int64_t max_valid_rows) {
     Plan p;
     bool use_compact = false;

@@ -101,3 +101,14 @@ def test_accumulator_choice(L):
     assert binding.get_backward_accumulator(16384, 4096, 32000) == 2
     with pytest.raises(binding.CCEError):
         binding.set_backward_accumulator(3)
+
+
+def test_row_skipping_tiling_query(L):
+    """Host-only: where rows are not skipped the row-skipping calls run the all-rows tiling; at the
+    headline shape with 15 % of the rows ignored they skip and fit the 28 row tiles into two blocks."""
+    assert binding.get_compact_tiling(8192, 896, 151936, 8192) == binding.get_backward_tiling(8192, 896, 151936)
+    assert binding.get_row_skipping(8192, 896, 151936, 6963)
+    a, b = binding.get_compact_tiling(8192, 896, 151936, 6963)
+    assert a == 14 and b >= 16
+    with pytest.raises(binding.CCEError):
+        binding.get_compact_tiling(8192, 100, 151936, 10)
