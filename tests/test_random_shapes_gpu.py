@@ -1,0 +1,80 @@
+"""Seeded sweep over random shapes, ignore fractions, forced tilings, contraction tiles,
+accumulator forms and both entry-point families (all rows / row skipping) against the oracle:
+the fixed shapes of the other parity tests were chosen by hand, these were not."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cce_oracle as O
+from paper_2601_02609_amd import inputs as I
+from tests.gpu_util import LOSS_ATOL, GRAD_RTOL, bf16_host, dev_inputs, rel_fro
+
+pytestmark = pytest.mark.gpu
+IGN = -100
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2601_02609_amd import binding
+    binding.lib()
+    return binding
+
+
+def draw_case(case):
+    rng = np.random.default_rng(977 + case)
+    N = int(rng.integers(1, 2600))
+    D = 64 * int(rng.integers(1, 17))
+    V = int(rng.integers(2, 5000))
+    frac = float(rng.choice([0.0, 0.1, 0.5, 0.9]))
+    rt = int(rng.integers(0, 4))
+    vt = int(rng.integers(1, 5)) if rt else 0
+    cols = int(rng.choice([0, 128, 256]))
+    acc = int(rng.choice([0, 1, 2]))
+    skip = int(rng.choice([0, 2]))
+    slack = int(rng.integers(0, 3))
+    return N, D, V, frac, rt, vt, cols, acc, skip, slack
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_case(B, case):
+    N, D, V, frac, rt, vt, cols, acc, skip, slack = draw_case(case)
+    print(f"[random] case {case}: N={N} D={D} V={V} ignore={frac} tiling=({rt},{vt}) tile cols={cols} "
+          f"accumulator={acc} row skipping={skip}", flush=True)
+    w = I.make_workload(I.custom_spec(N, D, V, seed=1000 + case, ignore_frac=frac))
+    H, W, y = dev_inputs(w)
+    o_loss, o_lse = O.forward(w.hidden, w.weight, w.labels, IGN)
+    o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, w.dloss_var, IGN)
+    ign = w.labels == IGN
+    dl = torch.from_numpy(w.dloss_var).cuda()
+    try:
+        B.set_backward_tiling(rt, vt)
+        B.set_backward_gemm_tile(cols)
+        B.set_backward_accumulator(acc)
+        B.set_row_skipping(skip)
+        for family in ("all rows", "row skipping"):
+            loss = torch.full((N,), 7.0, device="cuda")
+            lse = torch.full((N,), 7.0, device="cuda")
+            dH = torch.full((N, D), 3.0, dtype=torch.bfloat16, device="cuda")
+            dW = torch.full((V, D), 3.0, dtype=torch.float32, device="cuda")
+            if family == "all rows":
+                ws = B.alloc_workspace(N, D, V)
+                B.cce_forward(H, W, y, IGN, workspace=ws, loss=loss, lse=lse)
+                B.cce_backward(H, W, y, lse, dl, IGN, workspace=ws, d_hidden=dH, d_weight=dW)
+            else:
+                bound = int(w.n_valid) + slack
+                ws = B.alloc_compact_workspace(N, D, V, bound)
+                B.cce_forward_compact(H, W, y, bound, IGN, workspace=ws, loss=loss, lse=lse)
+                B.cce_backward_compact(H, W, y, lse, dl, bound, IGN, workspace=ws, d_hidden=dH, d_weight=dW)
+            torch.cuda.synchronize()
+            assert B.read_status(ws) == 0, family
+            g_loss, g_lse, g_dH = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), bf16_host(dH)
+            assert np.max(np.abs(g_loss - o_loss)) <= LOSS_ATOL, family
+            assert np.max(np.abs(g_lse[~ign] - o_lse[~ign])) <= LOSS_ATOL, family
+            assert np.all(g_loss[ign] == 0.0) and np.all(g_dH[ign] == 0.0), family
+            assert rel_fro(g_dH, o_dH) <= GRAD_RTOL, family
+            assert rel_fro(dW.cpu().numpy().astype(np.float64), o_dW) <= GRAD_RTOL, family
+    finally:
+        B.set_backward_tiling(0, 0)
+        B.set_backward_gemm_tile(0)
+        B.set_backward_accumulator(0)
+        B.set_row_skipping(0)
