@@ -28,6 +28,15 @@ What it computes, and where the paper defines it:
                    operands is taken, so the two gradient contractions are those of the bf16
                    path).
 
+* printed quantiser  ``quantize_blocks_printed`` is the block-wise E4M3 quantisation algorithm exactly as
+                   the paper prints it -- scale = amax / 448 as a real number (float64 here), block / scale clamped to +-448 and rounded to
+                   E4M3 -- with no power-of-two rounding of the scale.  The GPU path does not
+                   compute it (its matrix instruction takes exponent-only scales); it exists so that
+                   the distance between the reading above and the paper's own quantiser is a tested
+                   number: tests bound the logit and loss differences between the two.  Readings:
+                   round to nearest even (the paper does not say); an all-zero block gets scale 0 and
+                   codes 0 (the printed division would be 0 / 0).
+
 Pinned by tests/test_fp8_oracle_pins.py: the format constants the paper states, all 256 codes
 round-tripping, torch's float8_e4m3fn conversion on the CPU (round to nearest even), the
 quantiser's invariants and error bound, and agreement of the FP8 forward with the bf16 oracle
@@ -38,7 +47,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = ["BLOCK", "E4M3_MAX", "e4m3_decode", "e4m3_encode", "quantize_blocks", "dequantize",
-           "logits", "forward", "backward"]
+           "logits", "forward", "backward", "quantize_blocks_printed", "dequantize_printed", "forward_from_logits"]
 
 BLOCK = 128
 E4M3_MAX = 448.0
@@ -103,6 +112,47 @@ def dequantize(codes: np.ndarray, exps: np.ndarray) -> np.ndarray:
 
 def logits(hq, hs, wq, ws) -> np.ndarray:
     return dequantize(hq, hs) @ dequantize(wq, ws).T
+
+
+def quantize_blocks_printed(x_bits: np.ndarray):
+    """The paper's block-wise E4M3 quantisation algorithm as printed: per block of 128,
+    scale = amax / 448, codes = E4M3(clamp(block / scale, -448, 448)).  bf16 bit patterns
+    [rows, D] -> (codes uint8 [rows, D], scales float64 [rows, D / 128]); value = decode(code) * scale.
+
+    block / scale is formed as block * 448 / amax: the product is exact in float64 (bf16 values have
+    8 significant bits), so one correctly rounded division stands for the real-number quotient and
+    exact ties (e.g. block = 3/8 amax -> 168, midway between 160 and 176) stay ties."""
+    x = _widen_bf16(x_bits)
+    rows, D = x.shape
+    if D % BLOCK:
+        raise ValueError("D must be a multiple of 128")
+    xb = x.reshape(rows, D // BLOCK, BLOCK)
+    amax = np.abs(xb).max(axis=2)
+    scale = amax / E4M3_MAX
+    with np.errstate(divide="ignore", invalid="ignore"):
+        scaled = np.where(amax[:, :, None] > 0.0, xb * E4M3_MAX / amax[:, :, None], 0.0)
+    scaled = np.clip(scaled, -E4M3_MAX, E4M3_MAX)
+    return e4m3_encode(scaled).reshape(rows, D), scale
+
+
+def dequantize_printed(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    rows, D = codes.shape
+    v = e4m3_decode(codes).reshape(rows, D // BLOCK, BLOCK)
+    return (v * np.asarray(scales, dtype=np.float64)[:, :, None]).reshape(rows, D)
+
+
+def forward_from_logits(Z, labels, ignore_index=-100):
+    """loss = lse - z_label and lse (float64) of materialised logits; ignored rows give 0, 0."""
+    labels = np.asarray(labels, dtype=np.int64)
+    valid = labels != ignore_index
+    m = Z.max(axis=1)
+    lse_all = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+    idx = np.nonzero(valid)[0]
+    loss = np.zeros(len(labels))
+    lse = np.zeros(len(labels))
+    lse[idx] = lse_all[idx]
+    loss[idx] = lse_all[idx] - Z[idx, labels[idx]]
+    return loss, lse
 
 
 def forward(hq, hs, wq, ws, labels, ignore_index=-100):

@@ -117,6 +117,47 @@ def test_bound_too_small_is_flagged(B):
     assert np.abs(loss[kept] - o_loss[kept]).max() <= LOSS_ATOL
 
 
+def test_dropped_rows_give_zeros_not_stale_memory(B):
+    """A bound that is too small drops the last valid rows: their loss, lse and dHidden rows are
+    zero (the sentinels the outputs were prefilled with are gone) and the status bit is set."""
+    w = I.make_workload(I.custom_spec(700, 128, 3000, seed=57, ignore_frac=0.2))
+    drop = 9
+    loss, lse, dH, dW, st_f, st_b = run_compact(B, w, w.dloss_mean, w.n_valid - drop)
+    assert st_f & ROW_BOUND and st_b & ROW_BOUND
+    valid = np.nonzero(w.labels != IGN)[0]
+    dropped, kept = valid[-drop:], valid[:-drop]
+    assert np.all(loss[dropped] == 0.0) and np.all(lse[dropped] == 0.0) and np.all(dH[dropped] == 0.0)
+    assert np.all(loss[kept] != 7.0) and np.all(np.abs(dH[kept]).sum(axis=1) > 0)
+    # what was computed is the gradient of the kept rows alone
+    lab = w.labels.copy()
+    lab[dropped] = IGN
+    o_dH, o_dW = O.backward(w.hidden, w.weight, lab, w.dloss_mean, IGN)
+    assert rel_fro(dH, o_dH) <= GRAD_RTOL and rel_fro(dW, o_dW) <= GRAD_RTOL
+
+
+@pytest.mark.parametrize("slack", [0, 100])
+def test_ignored_rows_are_inert_even_with_nan_hidden(B, slack):
+    """The row-skipping path never loads the hidden row of an ignored token: NaN / Inf there (row 0
+    included, and with a loose bound, where compact rows behind the last valid one exist) and NaN
+    in dloss change no bit of any output."""
+    spec = I.custom_spec(700, 128, 1500, seed=58, ignore_frac=0.3)
+    w = I.make_workload(spec)
+    w.labels[0] = IGN
+    n_valid = int((w.labels != IGN).sum())
+    assert n_valid + slack < spec.N                      # a bound >= N would switch row skipping off
+    base = run_compact(B, w, w.dloss_mean, n_valid + slack)
+    w2 = I.make_workload(spec)
+    w2.labels[0] = IGN
+    ign = w2.labels == IGN
+    w2.hidden[ign] = 0x7FC0                              # bf16 NaN
+    w2.hidden[np.nonzero(ign)[0][1]] = 0x7F80            # +Inf
+    dl = w.dloss_mean.copy()
+    dl[ign] = np.nan
+    got = run_compact(B, w2, dl, n_valid + slack)
+    for a, b in zip(base[:4], got[:4]):
+        assert np.all(np.isfinite(b)) and np.array_equal(a, b)
+
+
 def test_no_valid_rows_and_bad_labels(B):
     w = I.make_workload(I.custom_spec(300, 64, 500, seed=54, ignore_frac=1.0))
     loss, lse, dH, dW, st_f, st_b = run_compact(B, w, w.dloss_mean, 0)

@@ -1,13 +1,14 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Configuration 2 (the headline shape) is compared against the full fp64 oracle, every
-element.  Configurations 3-5 are too large for a full fp64 pass within a test, so they are
-checked on outputs the oracle can compute one by one:
+element, through both entry-point families (all rows; row skipping as bench.py calls it).
+Configurations 3-5 are too large for a full fp64 backward within a test, so they are checked on
+outputs the oracle can compute one by one, with the benchmark's upstream gradient on every row:
   * loss / lse and dHidden rows of a seeded sample of token rows (each row's oracle value
     needs only that row and the full vocabulary, so it is exact);
-  * rows of dW on a seeded sample of vocabulary ids, from a second backward whose upstream
-    gradient is non-zero only on a seeded subset of token rows (all N rows still flow
-    through the kernels; the oracle then needs only that subset);
+  * rows of dW on a seeded sample of vocabulary ids, every token row contributing (the oracle
+    forms its fp64 softmax over all N rows and the whole vocabulary and contracts the sampled
+    columns of the gradient with the hidden states);
 and on properties that hold at any size: ignored rows give exact zeros, the columns of dW
 sum to zero (each row of softmax - onehot sums to zero), everything is finite.
 """
@@ -30,7 +31,20 @@ def B():
     return binding
 
 
+def _rel_fro_dw_slabs(dW_dev, o_dW, V):
+    """relative Frobenius error of a device fp32 dW against the oracle's, in slabs (bounds host memory)"""
+    num = den = 0.0
+    for r0 in range(0, V, 16384):
+        g = dW_dev[r0:r0 + 16384].cpu().numpy().astype(np.float64)
+        num += float(((g - o_dW[r0:r0 + 16384]) ** 2).sum())
+        den += float((o_dW[r0:r0 + 16384] ** 2).sum())
+    return (num / den) ** 0.5
+
+
 def test_config2_full_oracle(B):
+    """Both entry-point families at the headline shape, every element against the full fp64 oracle:
+    cce_forward + cce_backward (all rows), and cce_forward_compact + cce_backward_compact as bench.py
+    calls them (exact count of valid rows, automatic tiling, mean upstream gradient on every row)."""
     w = I.make_config("qwen05b")
     N, D, V = w.spec.N, w.spec.D, w.spec.V
     print(f"[full] qwen05b N={N} D={D} V={V}: GPU", flush=True)
@@ -42,83 +56,110 @@ def test_config2_full_oracle(B):
     dH, dW = B.cce_backward(H, W, y, lse, dl, IGN, workspace=ws)
     torch.cuda.synchronize()
     assert B.read_status(ws) == 0
-    g_loss, g_lse = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
-    g_dH = bf16_host(dH)
+
+    # the row-skipping entry points, outputs prefilled with a sentinel
+    bound = w.n_valid
+    assert B.get_row_skipping(N, D, V, bound), "row skipping is what the benchmark runs at this shape"
+    tiling = B.get_compact_tiling(N, D, V, bound)
+    print(f"[full] qwen05b: row-skipping entry points, bound={bound}, tiling={tiling}", flush=True)
+    wc = B.alloc_compact_workspace(N, D, V, bound)
+    assert wc.numel() <= 0.01 * B.materialised_logit_bytes(N, V)
+    c_loss = torch.full((N,), 7.0, device="cuda")
+    c_lse = torch.full((N,), 7.0, device="cuda")
+    c_dH = torch.full((N, D), 3.0, dtype=torch.bfloat16, device="cuda")
+    c_dW = torch.full((V, D), 3.0, dtype=torch.float32, device="cuda")
+    B.cce_forward_compact(H, W, y, bound, IGN, workspace=wc, loss=c_loss, lse=c_lse)
+    B.cce_backward_compact(H, W, y, c_lse, dl, bound, IGN, workspace=wc, d_hidden=c_dH, d_weight=c_dW)
+    torch.cuda.synchronize()
+    assert B.read_status(wc) == 0
+
+    ign = w.labels == IGN
     print("[full] qwen05b: oracle forward", flush=True)
     o_loss, o_lse = O.forward(w.hidden, w.weight, w.labels, IGN)
-    e_loss, e_lse = np.abs(g_loss - o_loss).max(), np.abs(g_lse - o_lse).max()
-    print(f"[full] qwen05b: max|dloss|={e_loss:.2e} max|dlse|={e_lse:.2e}; oracle backward", flush=True)
-    assert e_loss <= LOSS_ATOL and e_lse <= LOSS_ATOL
-    ign = w.labels == IGN
-    assert np.all(g_loss[ign] == 0) and np.all(g_lse[ign] == 0) and np.all(g_dH[ign] == 0)
+    for tag, l_dev, s_dev, h_dev in (("all rows", loss, lse, dH), ("row skipping", c_loss, c_lse, c_dH)):
+        g_loss, g_lse = l_dev.cpu().numpy().astype(np.float64), s_dev.cpu().numpy().astype(np.float64)
+        e_loss, e_lse = np.abs(g_loss - o_loss).max(), np.abs(g_lse - o_lse).max()
+        print(f"[full] qwen05b {tag}: max|dloss|={e_loss:.2e} max|dlse|={e_lse:.2e}", flush=True)
+        assert e_loss <= LOSS_ATOL and e_lse <= LOSS_ATOL
+        assert np.all(g_loss[ign] == 0) and np.all(g_lse[ign] == 0) and np.all(bf16_host(h_dev)[ign] == 0)
+    print("[full] qwen05b: oracle backward", flush=True)
     o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, w.dloss_mean, IGN)
-    e_dH = rel_fro(g_dH, o_dH)
-    del o_dH
-    # compare dW in slabs to bound host memory
-    num = den = 0.0
-    for r0 in range(0, V, 16384):
-        g = dW[r0:r0 + 16384].cpu().numpy().astype(np.float64)
-        num += float(((g - o_dW[r0:r0 + 16384]) ** 2).sum())
-        den += float((o_dW[r0:r0 + 16384] ** 2).sum())
-    e_dW = (num / den) ** 0.5
-    print(f"[full] qwen05b: relF(dH)={e_dH:.2e} relF(dW)={e_dW:.2e}", flush=True)
-    assert e_dH <= GRAD_RTOL and e_dW <= GRAD_RTOL
+    for tag, h_dev, w_dev in (("all rows", dH, dW), ("row skipping", c_dH, c_dW)):
+        e_dH = rel_fro(bf16_host(h_dev), o_dH)
+        e_dW = _rel_fro_dw_slabs(w_dev, o_dW, V)
+        print(f"[full] qwen05b {tag}: relF(dH)={e_dH:.2e} relF(dW)={e_dW:.2e}", flush=True)
+        assert e_dH <= GRAD_RTOL and e_dW <= GRAD_RTOL
 
 
 @pytest.mark.parametrize("name", ["1b", "7b", "smallv"])
 def test_large_configs_sampled(B, name):
+    """Configurations 3-5 with the benchmark's upstream gradient (mean reduction on every row).  A full
+    fp64 backward is out of reach, so: loss / lse / dHidden on sampled token rows (exact for those
+    rows), and rows of the REAL dW -- every token row contributing -- on a seeded sample of
+    vocabulary ids, for which the oracle runs its fp64 softmax over all N rows and the whole
+    vocabulary.  Where row skipping is what the library chooses (configuration 5), the row-skipping
+    entry points go through the same checks."""
     w = I.make_config(name)
     N, D, V = w.spec.N, w.spec.D, w.spec.V
     print(f"[full] {name} N={N} D={D} V={V}: GPU", flush=True)
     H, W, y = dev_inputs(w)
-    ws = B.alloc_workspace(N, D, V)
-    loss, lse = B.cce_forward(H, W, y, IGN, workspace=ws)
     dl = torch.from_numpy(w.dloss_mean).cuda()
-    dH, dW = B.cce_backward(H, W, y, lse, dl, IGN, workspace=ws)
-    torch.cuda.synchronize()
-    assert B.read_status(ws) == 0
-
-    g_loss, g_lse = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
     ign = w.labels == IGN
-    assert np.all(np.isfinite(g_loss)) and np.all(g_loss[ign] == 0) and np.all(g_lse[ign] == 0)
-    assert bool(torch.isfinite(dW).all()) and bool(torch.isfinite(dH.float()).all())
-    if ign.any():
-        ign_idx = torch.from_numpy(np.nonzero(ign)[0]).cuda()
-        assert bool((dH[ign_idx] == 0).all())
-    # columns of dW sum to zero (up to fp32/bf16 rounding of ~N terms per entry)
-    colsum = dW.double().sum(dim=0).abs().max().item()
-    scale = dW.double().abs().sum(dim=0).max().item()
-    print(f"[full] {name}: max|colsum dW|={colsum:.3e} vs sum|dW|={scale:.3e}", flush=True)
-    assert colsum <= 2e-3 * scale
-
     rng = np.random.default_rng(123)
     rows = np.unique(np.concatenate([[0, N - 1, 255, 256], rng.choice(N, 44, replace=False),
                                      np.nonzero(ign)[0][:4]])).astype(np.int64)
-    print(f"[full] {name}: oracle on {rows.size} sampled rows", flush=True)
+    # vocabulary sample: edges of the first tiles and of the matrix, the most frequent labels
+    # (ids 0, 1, 2, ... under the Zipf recipe: rows of dW with large one-hot parts), labels of the
+    # sampled token rows, and a uniform draw (mostly never-labelled ids: pure softmax rows)
+    vrows = np.unique(np.concatenate([[0, 1, 2, 3, 255, 256, 257, V - 2, V - 1], np.arange(16),
+                                      w.labels[rows][w.labels[rows] >= 0], rng.choice(V, 560, replace=False)])).astype(np.int64)
+
+    runs = []
+    ws = B.alloc_workspace(N, D, V)
+    assert ws.numel() <= max(0.01 * B.materialised_logit_bytes(N, V), 48e6)
+    loss, lse = B.cce_forward(H, W, y, IGN, workspace=ws)
+    dH, dW = B.cce_backward(H, W, y, lse, dl, IGN, workspace=ws)
+    torch.cuda.synchronize()
+    assert B.read_status(ws) == 0
+    runs.append(("all rows", loss, lse, dH, dW))
+    if B.get_row_skipping(N, D, V, w.n_valid):
+        wc = B.alloc_compact_workspace(N, D, V, w.n_valid)
+        c_loss = torch.full((N,), 7.0, device="cuda")
+        c_lse = torch.full((N,), 7.0, device="cuda")
+        c_dH = torch.full((N, D), 3.0, dtype=torch.bfloat16, device="cuda")
+        c_dW = torch.full((V, D), 3.0, dtype=torch.float32, device="cuda")
+        B.cce_forward_compact(H, W, y, w.n_valid, IGN, workspace=wc, loss=c_loss, lse=c_lse)
+        B.cce_backward_compact(H, W, y, c_lse, dl, w.n_valid, IGN, workspace=wc, d_hidden=c_dH, d_weight=c_dW)
+        torch.cuda.synchronize()
+        assert B.read_status(wc) == 0
+        print(f"[full] {name}: row skipping chosen, tiling {B.get_compact_tiling(N, D, V, w.n_valid)}", flush=True)
+        runs.append(("row skipping", c_loss, c_lse, c_dH, c_dW))
+
+    print(f"[full] {name}: oracle on {rows.size} sampled token rows", flush=True)
     o_loss, o_lse = O.forward(w.hidden[rows], w.weight, w.labels[rows], IGN)
     o_dH, _ = O.backward(w.hidden[rows], w.weight, w.labels[rows], w.dloss_mean[rows], IGN)
-    e_loss, e_lse = np.abs(g_loss[rows] - o_loss).max(), np.abs(g_lse[rows] - o_lse).max()
-    g_dH = bf16_host(dH[torch.from_numpy(rows).cuda()])
-    e_dH = rel_fro(g_dH, o_dH)
-    print(f"[full] {name}: max|dloss|={e_loss:.2e} max|dlse|={e_lse:.2e} relF(dH rows)={e_dH:.2e}", flush=True)
-    assert e_loss <= LOSS_ATOL and e_lse <= LOSS_ATOL and e_dH <= GRAD_RTOL
-    del dH
+    print(f"[full] {name}: oracle dW on {vrows.size} vocabulary rows from all {N} token rows", flush=True)
+    o_dWr = O.dweight_rows(w.hidden, w.weight, w.labels, w.dloss_mean, vrows, IGN, row_block=1024)
 
-    # dW: upstream gradient only on a subset of rows; the oracle then needs only those rows
-    sub = np.sort(rng.choice(np.nonzero(~ign)[0], 384, replace=False))
-    dl2 = np.zeros(N, dtype=np.float32)
-    dl2[sub] = w.dloss_var[sub]
-    dH2, dW2 = B.cce_backward(H, W, y, lse, torch.from_numpy(dl2).cuda(), IGN, workspace=ws, d_weight=dW)
-    torch.cuda.synchronize()
-    vrows = np.unique(np.concatenate([[0, 1, 255, 256, V - 1, V - 2], w.labels[sub][:200],
-                                      rng.choice(V, 600, replace=False)])).astype(np.int64)
-    print(f"[full] {name}: oracle dW on {vrows.size} vocabulary rows from {sub.size} token rows", flush=True)
-    o_dWr = O.dweight_rows(w.hidden[sub], w.weight, w.labels[sub], dl2[sub], vrows, IGN, row_block=128)
-    g_dWr = dW2[torch.from_numpy(vrows).cuda()].cpu().numpy().astype(np.float64)
-    e_dW = rel_fro(g_dWr, o_dWr)
-    print(f"[full] {name}: relF(dW rows)={e_dW:.2e}", flush=True)
-    assert e_dW <= GRAD_RTOL
-    # rows of dH2 outside the subset have dloss = 0: exactly zero gradient
-    mask = np.ones(N, bool)
-    mask[sub] = False
-    assert bool((dH2[torch.from_numpy(np.nonzero(mask)[0][:4096]).cuda()] == 0).all())
+    for tag, l_dev, s_dev, h_dev, w_dev in runs:
+        g_loss, g_lse = l_dev.cpu().numpy().astype(np.float64), s_dev.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(g_loss)) and np.all(g_loss[ign] == 0) and np.all(g_lse[ign] == 0)
+        assert bool(torch.isfinite(w_dev).all()) and bool(torch.isfinite(h_dev.float()).all())
+        if ign.any():
+            assert bool((h_dev[torch.from_numpy(np.nonzero(ign)[0]).cuda()] == 0).all())
+        # columns of dW sum to zero (up to fp32/bf16 rounding of ~N terms per entry)
+        colsum = w_dev.double().sum(dim=0).abs().max().item()
+        scale = w_dev.double().abs().sum(dim=0).max().item()
+        assert colsum <= 2e-3 * scale
+        e_loss, e_lse = np.abs(g_loss[rows] - o_loss).max(), np.abs(g_lse[rows] - o_lse).max()
+        e_dH = rel_fro(bf16_host(h_dev[torch.from_numpy(rows).cuda()]), o_dH)
+        g_dWr = w_dev[torch.from_numpy(vrows).cuda()].cpu().numpy().astype(np.float64)
+        e_dW = rel_fro(g_dWr, o_dWr)
+        # the frequent labels dominate the norm: check the never-labelled rows on their own as well
+        quiet = ~np.isin(vrows, w.labels[~ign])
+        e_dWq = rel_fro(g_dWr[quiet], o_dWr[quiet])
+        print(f"[full] {name} {tag}: max|dloss|={e_loss:.2e} max|dlse|={e_lse:.2e} relF(dH rows)={e_dH:.2e} "
+              f"relF(dW rows)={e_dW:.2e} relF(never-labelled dW rows, {int(quiet.sum())})={e_dWq:.2e} "
+              f"max|colsum dW|={colsum:.2e}", flush=True)
+        assert e_loss <= LOSS_ATOL and e_lse <= LOSS_ATOL and e_dH <= GRAD_RTOL
+        assert e_dW <= GRAD_RTOL and e_dWq <= GRAD_RTOL

@@ -180,6 +180,21 @@ def test_zero_weight_gives_ln_V(B):
     assert rel_fro(dW, o_dW) <= GRAD_RTOL
 
 
+def test_zero_hidden_gives_ln_V(B):
+    """H = 0: every logit is 0, so lse = loss = ln V for every valid row, dW = 0 exactly (it is a
+    sum of multiples of zero rows) and dH_i = dloss_i (mean_v W_v - W_{y_i})."""
+    w = I.make_workload(I.custom_spec(300, 128, 1000, seed=12, ignore_frac=0.1))
+    w.hidden[:] = 0
+    loss, lse, dH, dW = run_both(B, w, w.dloss_mean)
+    valid = w.labels != IGN
+    assert np.abs(loss[valid] - math.log(1000)).max() <= 1e-4
+    assert np.abs(lse[valid] - math.log(1000)).max() <= 1e-4
+    assert np.all(loss[~valid] == 0.0) and np.all(dH[~valid] == 0.0)
+    assert np.all(dW == 0.0)
+    o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, w.dloss_mean, IGN)
+    assert np.all(o_dW == 0.0) and rel_fro(dH, o_dH) <= GRAD_RTOL
+
+
 def test_large_logits_do_not_overflow(B):
     N, D, V = 64, 64, 300
     rng = np.random.default_rng(0)
@@ -195,7 +210,10 @@ def test_large_logits_do_not_overflow(B):
 
 
 def test_ignored_rows_are_inert(B):
-    """Garbage hidden rows and NaN/Inf dloss at ignored positions change nothing."""
+    """Garbage (finite) hidden rows and NaN/Inf dloss at ignored positions change nothing.  (A NaN in
+    the hidden row of an ignored token is outside this entry point's contract: every row goes
+    through the dense dW = G^T H product, where it would meet the row's zero gradient.  The
+    row-skipping entry points never load such rows: tests/test_compact_gpu.py.)"""
     w = I.make_workload(I.custom_spec(300, 64, 600, seed=6, ignore_frac=0.3))
     base = run_both(B, w, w.dloss_mean)
     w2 = I.make_workload(I.custom_spec(300, 64, 600, seed=6, ignore_frac=0.3))
