@@ -35,7 +35,10 @@
  *     outside [0, V) that is not `ignore_index` is treated the same way and sets
  *     CCE_STATUS_BAD_LABEL in the workspace status word (see cce_read_status).
  *   - Every call returns CCE_OK (0) or a negative error code; nothing throws or
- *     aborts across this boundary.  On an error return nothing was enqueued.
+ *     aborts across this boundary.  On CCE_ERR_INVALID / CCE_ERR_UNSUPPORTED nothing was
+ *     enqueued.  CCE_ERR_HIP means a launch of THIS call failed (errors left by earlier HIP
+ *     calls of the thread are dropped at entry, not reported); launches before the failing
+ *     one may have been enqueued and the outputs are then undefined.
  *   - `workspace` is caller-owned device scratch of at least
  *     cce_workspace_bytes(N, D, V) bytes, 256-byte aligned.  Its size is
  *     O(N*D + tile): per-row partial (max, sum-exp, logit-sum) triples, the fp32
@@ -160,8 +163,9 @@ int cce_backward_ex(const void* hidden, const void* weight, const int32_t* label
  * later calls of this process, cce_workspace_bytes included; (0, 0) restores the automatic
  * choice, which stays inside the workspace budget (1 % of the materialised logits, at
  * least 48 MB).  The chunking is a free parameter of the chunk-level backward
- * algorithm: results agree across tilings up to fp32 summation order.  Host state only;
- * not thread safe.  Returns CCE_ERR_INVALID for negative values or when only one is 0.  A forced
+ * algorithm: results agree across tilings up to fp32 summation order.  Process-wide host
+ * state (an atomic: it may be set from any thread and every call reads it once, so a plan never
+ * mixes two settings; size the workspace and compute under the SAME setting).  Returns CCE_ERR_INVALID for negative values or when only one is 0.  A forced
  * tiling whose gradient chunk (rows x columns x 2 bytes) would reach 4 GiB makes the calls that
  * use it fail with CCE_ERR_INVALID (cce_workspace_bytes returns 0).
  */
@@ -173,7 +177,8 @@ int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int
 
 /* Tuning / testing aid like cce_set_backward_tiling: force the output tile of the two gradient
  * contractions to 256 x tile_cols, tile_cols = 128 or 256; 0 restores the automatic choice.
- * Results agree across the two up to fp32 summation order.  Host state only; not thread safe. */
+ * Results agree across the two up to fp32 summation order.  Process-wide host state, like the
+ * forced tiling. */
 int cce_set_backward_gemm_tile(int tile_cols);
 
 /* Tuning / testing aid: how the running sum of dHidden over the vocabulary chunks is kept --
@@ -197,7 +202,8 @@ int cce_get_backward_gemm_tile(int64_t N, int64_t D, int64_t V, int* tile_rows, 
  * families between cce_profile_begin() and cce_profile_end().  cce_profile_end()
  * synchronises on the recorded events and fills, per family (CCE_KERNEL_*), the summed
  * milliseconds and the number of launches; both arrays are HOST arrays of
- * CCE_KERNEL_FAMILIES entries.  Host-side state only; use from one thread at a time.
+ * CCE_KERNEL_FAMILIES entries.  Process-wide host state behind a lock: launches of every thread
+ * between the two calls are recorded; begin / end themselves belong to one measuring thread.
  */
 enum {
     CCE_KERNEL_LSE_PARTIAL = 0,   /* forward logit tiles + online log-sum-exp            */

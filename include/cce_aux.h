@@ -128,6 +128,15 @@ int cce_adamw_step(float* param, void* param_bf16, const float* grad, float* m, 
  */
 int cce_mfma_probe(int workgroups, int iters, float* sink, void* stream);
 
+/*
+ * Measurement aid: the same register-only loop (same flop count) with every lane's operand
+ * fragments loaded once, before the loop, from `operands` -- device, bf16, 512 x 48 values
+ * (48 KB), 16-byte aligned, read by every workgroup.  The instruction stream does not depend on
+ * the data, so timing it on random values against constants or zeros separates what the
+ * device's power management does with operand activity from what the schedule costs.
+ */
+int cce_mfma_probe_data(int workgroups, int iters, const void* operands, float* sink, void* stream);
+
 /* Compute units and peak shader clock (kHz) of the current device, from the HIP device
  * attributes: compute units x 4096 bf16 flop per clock x clock is the nominal dense MFMA peak.
  * Both outputs are host ints. */

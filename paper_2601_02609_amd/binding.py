@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = [
     "cce_rmsnorm_workspace_bytes", "cce_rmsnorm_forward", "cce_rmsnorm_backward",
     "cce_rmsnorm_residual_forward", "cce_rmsnorm_residual_backward",
     "cce_sumsq_workspace_bytes", "cce_grad_sumsq", "cce_clip_coef", "cce_adamw_step",
-    "cce_mfma_probe", "cce_device_info",
+    "cce_mfma_probe", "cce_mfma_probe_data", "cce_device_info",
     # include/cce_shard.h
     "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
     # include/cce_compact.h
@@ -124,6 +124,8 @@ def lib() -> ctypes.CDLL:
     L.cce_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     L.cce_mfma_probe.restype = ctypes.c_int
     L.cce_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+    L.cce_mfma_probe_data.restype = ctypes.c_int
+    L.cce_mfma_probe_data.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp]
     L.cce_shard_forward.restype = ctypes.c_int
     L.cce_shard_forward.argtypes = [vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, vp, vp, sz, vp]
     L.cce_shard_merge.restype = ctypes.c_int
@@ -543,6 +545,24 @@ def mfma_probe_tflops(workgroups: int = 2048, iters: int = 4000) -> float:
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     _rc(lib().cce_mfma_probe(workgroups, iters, sink.data_ptr(), s), "cce_mfma_probe")
+    b.record()
+    torch.cuda.synchronize()
+    flops = float(workgroups) * 8 * iters * 8 * 32768
+    return flops / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
+def mfma_probe_data_tflops(operands: torch.Tensor, workgroups: int = 2048, iters: int = 4000) -> float:
+    """TFLOP/s of the register-only bf16 MFMA loop whose operand fragments are loaded once from
+    `operands` (bf16, at least 512 * 48 values) before the loop (measurement aid)."""
+    if operands.dtype != torch.bfloat16 or not operands.is_contiguous() or operands.numel() < 512 * 48:
+        raise ValueError("operands: expected a contiguous bfloat16 tensor of at least 24576 values")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    s = _stream_ptr(None)
+    _rc(lib().cce_mfma_probe_data(workgroups, 10, operands.data_ptr(), sink.data_ptr(), s), "cce_mfma_probe_data")
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    _rc(lib().cce_mfma_probe_data(workgroups, iters, operands.data_ptr(), sink.data_ptr(), s), "cce_mfma_probe_data")
     b.record()
     torch.cuda.synchronize()
     flops = float(workgroups) * 8 * iters * 8 * 32768

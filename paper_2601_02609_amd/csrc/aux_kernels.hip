@@ -413,6 +413,37 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float seed, 
     if (t == 12345.678f) sink[0] = t;                 // keeps the loop alive; never true in practice
 }
 
+// The same register-only loop with operands taken from memory ONCE, before the loop: four A and
+// two B fragments per lane (the 128 x 64 wavefront tile of the contraction kernels: 8 MFMAs on 6
+// fragments), 96 bytes per thread from operands[threadIdx.x * 48 ...].  What the buffer holds
+// (random normal values, constants, zeros) is the caller's choice: the instruction stream is the
+// same, so a difference in rate between buffers is the device's response to operand activity
+// (clock / power management), not to the schedule.
+__global__ __launch_bounds__(512) void mfma_probe_data_kernel(int iters, const uint16_t* __restrict__ operands,
+                                                              float* __restrict__ sink) {
+    abf16x8 a[4], b[2];
+    const au32x4* src = (const au32x4*)operands + (size_t)threadIdx.x * 6;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(abf16x8, src[i]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b[i] = __builtin_bit_cast(abf16x8, src[4 + i]);
+    af32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i >> 1], b[i & 1], acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    if (t == 12345.678f) sink[0] = t;
+}
+
 // ------------------------------------------------------------------------------------------
 // Block-wise E4M3 quantisation (block-wise quantisation algorithm of the paper's FP8 section:
 // blocks of 128 elements, one scale each, clamp to +-448), with the scale rounded up to a
@@ -620,6 +651,15 @@ int cce_device_info(int* compute_units, int* clock_khz) {
 int cce_mfma_probe(int workgroups, int iters, float* sink, void* stream_) {
     if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || !sink) return CCE_ERR_INVALID;
     hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream_, iters, 0.5f, sink);
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
+}
+
+int cce_mfma_probe_data(int workgroups, int iters, const void* operands, float* sink, void* stream_) {
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || !sink || !operands) return CCE_ERR_INVALID;
+    if ((uintptr_t)operands & 15) return CCE_ERR_INVALID;
+    hipLaunchKernelGGL(mfma_probe_data_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream_, iters,
+                       (const uint16_t*)operands, sink);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }

@@ -17,6 +17,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <math.h>
+#include <mutex>
 #include <vector>
 
 #include "../../include/cce.h"
@@ -573,6 +574,7 @@ struct GemmJob {
     float* out_f32; int64_t ld_out; int beta;
     uint16_t* out_hi; uint16_t* out_lo; int final;
     const int32_t* row_map;     // row skipping: out_hi row of tile row r is row_map[r] (-1: none); else nullptr
+    const char* zero_row;       // row skipping: a row of zeros, read by the dW job for k-rows that map to no row
 };
 
 // MODE bit 0: the launch's dH job uses the split running sum; bit 1: its bf16 rows go through
@@ -604,6 +606,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
             for (int i = threadIdx.x; i < j.b_k_n; i += kThreads) tab[i] = j.row_map[i];
             __syncthreads();
             Bop.kmap = tab;
+            Bop.kzero = j.zero_row;
         }
     }
     gemm_mainloop<Cfg, A_KMAJOR, false>(acc, Aop, Bop, j.k_total, smem);
@@ -757,11 +760,14 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
 // ------------------------------------------------------------------------------------------
 // One workgroup of 1024 threads: stable compaction of the valid rows (label in [0, V) and not
 // ignore_index).  At most max_rows are kept (more: CCE_STATUS_ROW_BOUND, the rest is dropped).
-// loss / lse of the rows that are not valid are set to zero when the pointers are given.
+// loss / lse of the rows that are not valid, and of valid rows that were dropped, are set to zero
+// when the pointers are given (a caller that does not poll the status word then sees a zero
+// contribution from a dropped row, not stale memory).  zero_row (optional): zero_row_len bf16 zeros
+// are written there.
 __global__ __launch_bounds__(1024) void row_scan_kernel(
         const int32_t* __restrict__ labels, int N, int V, int32_t ignore_index, int max_rows, int rows_pad,
         int32_t* __restrict__ perm, int32_t* __restrict__ count_out, int32_t* __restrict__ status,
-        float* __restrict__ loss, float* __restrict__ lse) {
+        float* __restrict__ loss, float* __restrict__ lse, uint16_t* __restrict__ zero_row, int zero_row_len) {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
     const int per = (N + 1023) / 1024;
@@ -785,14 +791,18 @@ __global__ __launch_bounds__(1024) void row_scan_kernel(
     const int total = part[1023];
     for (int i = i0; i < i1; ++i) {
         const int32_t y = labels[i];
+        bool zero = true;
         if (y != ignore_index && y >= 0 && y < V) {
-            if (pos < max_rows) perm[pos] = i;
+            if (pos < max_rows) { perm[pos] = i; zero = false; }
             ++pos;
-        } else if (loss) {
+        }
+        if (zero && loss) {
             loss[i] = 0.f;
             lse[i] = 0.f;
         }
     }
+    if (zero_row)
+        for (int c = tid; c < zero_row_len; c += 1024) zero_row[c] = 0;
     const int kept = total < max_rows ? total : max_rows;
     for (int r = kept + tid; r < rows_pad; r += 1024) perm[r] = -1;
     if (bad) atomicOr(status, CCE_STATUS_BAD_LABEL);
@@ -826,14 +836,19 @@ __global__ __launch_bounds__(256) void scatter_scalars_kernel(const int32_t* __r
     b[to] = b_c[r];
 }
 
-// Zero rows of dHidden for every row that is not valid.  One wavefront per row.
+// Zero rows of dHidden for every row that takes no part: label not valid, or a valid row that the
+// compaction dropped because the caller's bound was too small (the compaction is stable, so those
+// are the valid rows behind the last kept one).  One wavefront per row.
 __global__ __launch_bounds__(256) void zero_invalid_rows_kernel(const int32_t* __restrict__ labels, int N, int V,
-                                                                int32_t ignore_index, int D, uint16_t* __restrict__ out) {
+                                                                int32_t ignore_index, int D, uint16_t* __restrict__ out,
+                                                                const int32_t* __restrict__ perm, const int32_t* __restrict__ count) {
     const int l = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= N) return;
     const int32_t y = labels[r];
-    if (y != ignore_index && y >= 0 && y < V) return;
+    const int kept = count[0];
+    const int last_kept = kept > 0 ? perm[kept - 1] : -1;
+    if (y != ignore_index && y >= 0 && y < V && r <= last_kept) return;
     u32x4* dr = (u32x4*)(out + (size_t)r * D);
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (int c = l; c < (D >> 3); c += 64) dr[c] = z;
@@ -863,16 +878,22 @@ struct ProfState {
     }
 };
 static ProfState g_prof;
+static std::mutex g_prof_mu;            // guards g_prof (spans of concurrent callers interleave but stay consistent)
+static std::atomic<bool> g_prof_on{false};
 
 struct ProfSpan {
     int fam; hipStream_t s; size_t e0 = (size_t)-1;
     ProfSpan(int fam_, hipStream_t s_) : fam(fam_), s(s_) {
+        if (!g_prof_on.load(std::memory_order_relaxed)) return;
+        std::lock_guard<std::mutex> lock(g_prof_mu);
         if (!g_prof.on) return;
         e0 = g_prof.take();
         if (e0 != (size_t)-1) (void)hipEventRecord(g_prof.pool[e0], s);
     }
     ~ProfSpan() {
-        if (!g_prof.on || e0 == (size_t)-1) return;
+        if (e0 == (size_t)-1) return;
+        std::lock_guard<std::mutex> lock(g_prof_mu);
+        if (!g_prof.on) return;
         const size_t e1 = g_prof.take();
         if (e1 == (size_t)-1) return;
         (void)hipEventRecord(g_prof.pool[e1], s);
@@ -894,6 +915,11 @@ static int check_common(const void* hidden, const void* weight, const int32_t* l
     return CCE_OK;
 }
 
+// An error left behind by an earlier, unrelated HIP call of this thread must not be reported as
+// this call's: it is dropped before the first launch, so that the check after the last launch
+// sees this call's launches only.
+static inline void drop_stale_hip_error() { (void)hipGetLastError(); }
+
 template <class K>
 static bool allow_big_lds(K kernel, int bytes) {
     return hip_ok(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
@@ -904,10 +930,12 @@ constexpr int kGradTileLds = (256 * kGRowBytes + 256 > TileBig::kLdsBytes) ? 256
 // The MFMA kernels use more dynamic LDS than the default limit: raise it once per device
 // (not per call, so that the compute calls consist of kernel launches only).
 static bool ensure_kernel_attributes() {
+    static std::mutex mu;
     static bool done[64] = {};
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev))) return false;
     if (dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(mu);
     if (done[dev]) return true;
     if (!allow_big_lds(lse_partial_kernel<false, false>, TileBig::kLdsBytes)) return false;
     if (!allow_big_lds(lse_partial_kernel<true, false>, TileBig::kLdsBytes)) return false;
@@ -966,6 +994,7 @@ static bool variant_ok(float label_smoothing, float z_loss) {
 struct CompactCtx {
     Plan plan;                  // made for the compact rows
     const int32_t* perm;        // device: original row of each compact row, -1 for padding
+    const char* zero_row = nullptr;   // device: D bf16 zeros (backward only)
 };
 
 // Forward over the V rows of `weight`, which are the rows [v_off, v_off + V) of the full
@@ -1004,7 +1033,10 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
 
     const int32_t* fwd_perm = cc ? cc->perm : (const int32_t*)nullptr;
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
-    if (!cc) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    if (!cc) {
+        drop_stale_hip_error();
+        hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    }
     {
         ProfSpan span(CCE_KERNEL_LSE_PARTIAL, stream);
         if (fp8_in)
@@ -1054,6 +1086,7 @@ int cce_shard_merge(const float* stats, int P, const int32_t* labels, int64_t N,
         return CCE_ERR_INVALID;
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     hipStream_t stream = (hipStream_t)stream_;
+    drop_stale_hip_error();
     hipLaunchKernelGGL(shard_merge_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, stream,
                        (const float4*)stats, P, labels, (int)N, (int)V_total, ignore_index, label_smoothing, z_loss,
                        loss, lse, status);
@@ -1108,6 +1141,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
     uint16_t* G = (uint16_t*)(ws + p.off_g);
     // mean reduction: the common upstream gradient grad_scale / n_valid lives in the status block
     float* mean_scale = (float*)(ws + p.off_status + 64);
+    if (!cc) drop_stale_hip_error();
     if (!dloss)
         hipLaunchKernelGGL(mean_scale_kernel, dim3(1), dim3(1024), 0, stream,
                            labels, (int)N, (int)V_total, ignore_index, grad_scale, mean_scale);
@@ -1163,6 +1197,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dh.out_hi = (uint16_t*)dHidden + (cc ? (size_t)0 : (size_t)st.r0 * D); dh.out_lo = p.split_acc ? dh_lo : (uint16_t*)nullptr;
         dh.final = st.last_chunk ? 1 : 0;
         dh.row_map = cc ? cc->perm + st.r0 : (const int32_t*)nullptr;
+        dh.zero_row = nullptr;
         // dW chunk (+)= G^T * H_block   (M = chunk columns, K = rows, N = D)
         GemmJob dw;
         dw.a_kmajor = 0;
@@ -1174,6 +1209,7 @@ static int backward_impl(const void* hidden, const void* weight, const int32_t* 
         dw.out_f32 = dW + (size_t)st.v0 * D; dw.ld_out = D; dw.beta = (st.r0 > 0 || accumulate_dW) ? 1 : 0;
         dw.out_hi = nullptr; dw.out_lo = nullptr; dw.final = 0;
         dw.row_map = cc ? cc->perm + st.r0 : (const int32_t*)nullptr;
+        dw.zero_row = cc ? cc->zero_row : (const char*)nullptr;
         const bool dh_first = dh.k_total >= dw.k_total;          // longer reduction first
         const GemmJob& first = dh_first ? dh : dw;
         const GemmJob& second = dh_first ? dw : dh;
@@ -1220,8 +1256,9 @@ static bool choose_compact_plan(int64_t N, int64_t D, int64_t V, int64_t max_val
     if (!make_plan(N, D, V, &plain)) return false;
     *use_compact = false;
     *p = plain;
-    if (M < N && g_force_row_skipping != 1 && make_plan(M, D, V, &comp, N) &&
-        (g_force_row_skipping == 2 || comp.model_us + 30.0 < 0.98 * plain.model_us)) {
+    const int force = g_force_row_skipping.load(std::memory_order_relaxed);
+    if (M < N && force != 1 && make_plan(M, D, V, &comp, N) &&
+        (force == 2 || comp.model_us + 30.0 < 0.98 * plain.model_us)) {
         *use_compact = true;
         *p = comp;
     }
@@ -1247,7 +1284,7 @@ static int compact_plan(const void* hidden, const void* weight, const int32_t* l
 
 int cce_set_row_skipping(int mode) {
     if (mode < 0 || mode > 2) return CCE_ERR_INVALID;
-    g_force_row_skipping = mode;
+    g_force_row_skipping.store(mode, std::memory_order_relaxed);
     return CCE_OK;
 }
 
@@ -1300,9 +1337,11 @@ int cce_forward_compact(const void* hidden, const void* weight, const int32_t* l
     int32_t* status = (int32_t*)(ws + p.off_status);
     int32_t* perm = (int32_t*)(ws + p.off_perm);
     const int rows_pad = (int)p.rows_pad;
+    drop_stale_hip_error();
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
-                       (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status, loss, lse);
+                       (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status, loss, lse,
+                       (uint16_t*)nullptr, 0);
     // the kernels fetch hidden rows through perm and write loss / lse to the original rows
     cc.perm = perm;
     return forward_impl(hidden, weight, labels, M, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
@@ -1334,15 +1373,18 @@ int cce_backward_compact(const void* hidden, const void* weight, const int32_t* 
     float* lse_c = (float*)(ws + p.off_fa_c);
     float* dloss_c = (float*)(ws + p.off_fb_c);
     const int rows_pad = (int)p.rows_pad;
+    drop_stale_hip_error();
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
                        (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status,
-                       (float*)nullptr, (float*)nullptr);
+                       (float*)nullptr, (float*)nullptr, (uint16_t*)(ws + p.off_zero_row), (int)D);
     hipLaunchKernelGGL(gather_scalars_kernel, dim3((unsigned)((rows_pad + 255) / 256)), dim3(256), 0, stream,
                        (const int32_t*)perm, rows_pad, labels, ignore_index, labels_c, lse, lse_c, dloss, dloss_c);
     hipLaunchKernelGGL(zero_invalid_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
-                       labels, (int)N, (int)V, ignore_index, (int)D, (uint16_t*)dHidden);
+                       labels, (int)N, (int)V, ignore_index, (int)D, (uint16_t*)dHidden,
+                       (const int32_t*)perm, (const int32_t*)(ws + p.off_count));
     cc.perm = perm;
+    cc.zero_row = ws + p.off_zero_row;
     return backward_impl(hidden, weight, labels_c, lse_c, dloss_c, 1.f, M, D, V, 0, V, ignore_index, 0.f, 0.f,
                          dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_, &cc);
 }
@@ -1390,8 +1432,8 @@ int cce_backward(const void* hidden, const void* weight, const int32_t* labels,
 
 int cce_set_backward_tiling(int row_tiles, int vocab_tiles) {
     if (row_tiles < 0 || vocab_tiles < 0 || (row_tiles == 0) != (vocab_tiles == 0)) return CCE_ERR_INVALID;
-    g_force_row_tiles = row_tiles;
-    g_force_vocab_tiles = vocab_tiles;
+    if (row_tiles > 0x7fff || vocab_tiles > 0xffff) return CCE_ERR_INVALID;
+    g_force_tiling.store((row_tiles << 16) | vocab_tiles, std::memory_order_relaxed);
     return CCE_OK;
 }
 
@@ -1408,13 +1450,13 @@ int cce_get_backward_tiling(int64_t N, int64_t D, int64_t V, int* row_tiles, int
 
 int cce_set_backward_gemm_tile(int tile_cols) {
     if (tile_cols != 0 && tile_cols != 128 && tile_cols != 256) return CCE_ERR_INVALID;
-    g_force_gemm_cols = tile_cols;
+    g_force_gemm_cols.store(tile_cols, std::memory_order_relaxed);
     return CCE_OK;
 }
 
 int cce_set_backward_accumulator(int mode) {
     if (mode < 0 || mode > 2) return CCE_ERR_INVALID;
-    g_force_split_acc = mode;
+    g_force_split_acc.store(mode, std::memory_order_relaxed);
     return CCE_OK;
 }
 
@@ -1440,14 +1482,18 @@ int cce_get_backward_gemm_tile(int64_t N, int64_t D, int64_t V, int* tile_rows, 
 }
 
 int cce_profile_begin(void) {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
     g_prof.on = true;
     g_prof.used = 0;
     g_prof.spans.clear();
+    g_prof_on.store(true, std::memory_order_relaxed);
     return CCE_OK;
 }
 
 int cce_profile_end(double* ms_out, int64_t* launches_out) {
     if (!ms_out || !launches_out) return CCE_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    g_prof_on.store(false, std::memory_order_relaxed);
     g_prof.on = false;
     for (int i = 0; i < CCE_KERNEL_FAMILIES; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
     for (const ProfState::Span& sp : g_prof.spans) {

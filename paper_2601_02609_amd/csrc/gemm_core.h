@@ -99,7 +99,8 @@ struct OperandTile {
     uint32_t off[NL];       // K-major: clamped row offset + swizzled chunk; K-slow: clamped column offset
     int krow[NL];           // K-slow: k-row inside a slice handled by load i
     int k_last;             // K-slow: last valid k (rows beyond are clamped to it)
-    const CCE_LDS int32_t* kmap;   // K-slow, optional: k-row k is matrix row kmap[k] (row 0 where it holds -1)
+    const CCE_LDS int32_t* kmap;   // K-slow, optional: k-row k is matrix row kmap[k]; where it holds -1 the
+    const char* kzero;             // row is read from kzero instead: a row of zeros as long as a matrix row
 
     // free0: first free index of the tile; free_n: number of valid free indices in the matrix
     // (a multiple of 8, at least 8, for a K-slow operand); k_n: valid K extent.
@@ -111,6 +112,7 @@ struct OperandTile {
         ld_bytes = (uint32_t)(ld * 2);
         k_last = k_n - 1;
         kmap = nullptr;
+        kzero = nullptr;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         if (KMAJOR) {
             const int sw = ((lane >> 4) & 3) | ((wave & 1) << 2);
@@ -153,11 +155,13 @@ struct OperandTile {
             } else {
                 int k = k0 + krow[i];
                 k = k < k_last ? k : k_last;
-                if (kmap) {
-                    const int mapped = kmap[k];
-                    k = mapped < 0 ? 0 : mapped;
-                }
                 g = base + (size_t)((uint32_t)k * ld_bytes + off[i]);
+                if (kmap) {
+                    // a k-row that stands for no matrix row must not fetch one: whatever that row
+                    // holds (NaN included) would meet the other operand's zero in the MFMA
+                    const int mapped = kmap[k];
+                    g = mapped < 0 ? kzero + off[i] : base + (size_t)((uint32_t)mapped * ld_bytes + off[i]);
+                }
             }
             load16_to_lds(g, stage + (wave + 8 * i) * 1024);
         }

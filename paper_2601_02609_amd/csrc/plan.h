@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 
 #include "gemm_core.h"
 #include "host_util.h"
@@ -18,13 +19,16 @@ namespace cce {
 constexpr int kCompactMaxRowTiles = 16;
 constexpr int kRowTableBytes = kCompactMaxRowTiles * 256 * 4;
 
+// Compute units of the CURRENT device (looked up once per device ordinal; 256 if the query fails,
+// e.g. on a host without a GPU).
 static int device_cu_count() {
-    static int cached = 0;
-    if (cached > 0) return cached;
+    static std::atomic<int> cached[64];
     int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    const int have = cached[dev].load(std::memory_order_relaxed);
+    if (have > 0) return have;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
-    cached = n;
+    cached[dev].store(n, std::memory_order_relaxed);
     return n;
 }
 
@@ -39,6 +43,7 @@ struct Plan {
     // row skipping only (budget_rows != 0): compact-row bookkeeping
     int64_t rows_pad;           // compact rows rounded up to 256
     size_t off_count, off_perm, off_labels_c, off_fa_c, off_fb_c;
+    size_t off_zero_row;        // D zeros (bf16): what the dW contraction reads for a k-row that maps to no row
 };
 
 // Workspace budget: 1 % of the materialised fp32 logits, but never below a floor that
@@ -58,11 +63,23 @@ static GemmTile gemm_tile_of_kind(int kind) {
     return {1, TileNarrow::BM, TileNarrow::BN, 1.1};
 }
 
-// Backward tiling forced by cce_set_backward_tiling (0 = automatic).
-static int g_force_row_tiles = 0, g_force_vocab_tiles = 0;
-static int g_force_gemm_cols = 0;        // cce_set_backward_gemm_tile: 0 = automatic, 128 or 256
-static int g_force_split_acc = 0;        // cce_set_backward_accumulator: 0 = automatic, 1 = fp32, 2 = split
-static int g_force_row_skipping = 0;     // cce_set_row_skipping: 0 = automatic, 1 = never, 2 = whenever rows can be skipped
+// Process-wide tuning / testing knobs (0 = automatic).  Atomics: a knob may be set from any host
+// thread; every plan reads each knob once (Knobs::read) and the plan cache is keyed by what it read,
+// so a change between two calls can never mix two settings inside one plan.  (A caller that sizes
+// its workspace under one setting and computes under another still gets CCE_ERR_INVALID if the
+// workspace is too small: the knobs are aids for tests and measurements, not a per-call option.)
+static std::atomic<int> g_force_tiling{0};           // cce_set_backward_tiling: (row_tiles << 16) | vocab_tiles
+static std::atomic<int> g_force_gemm_cols{0};        // cce_set_backward_gemm_tile: 128 or 256
+static std::atomic<int> g_force_split_acc{0};        // cce_set_backward_accumulator: 1 = fp32, 2 = split
+static std::atomic<int> g_force_row_skipping{0};     // cce_set_row_skipping: 1 = never, 2 = whenever rows can be skipped
+struct Knobs {
+    int row_tiles, vocab_tiles, gemm_cols, split_acc;
+    static Knobs read() {
+        const int t = g_force_tiling.load(std::memory_order_relaxed);
+        return {t >> 16, t & 0xffff, g_force_gemm_cols.load(std::memory_order_relaxed),
+                g_force_split_acc.load(std::memory_order_relaxed)};
+    }
+};
 
 // Rough time model of the backward pipeline, in microseconds, used only to rank tilings.
 // One compute unit runs one workgroup at a time.  Measured on MI355X with random bf16 data:
@@ -120,13 +137,15 @@ struct BackwardModel {
 // workspace also holds the compact-row bookkeeping (row map and per-row scalars).
 static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_rows = 0) {
     if (N <= 0 || D <= 0 || V <= 0) return false;
-    struct Key { int64_t N, D, V, B; int fa, fb, fc, fs; Plan plan; bool valid; };
-    static thread_local Key cache = {0, 0, 0, 0, 0, 0, 0, 0, {}, false};
-    if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.B == budget_rows && cache.fa == g_force_row_tiles &&
-        cache.fb == g_force_vocab_tiles && cache.fc == g_force_gemm_cols && cache.fs == g_force_split_acc) { *p = cache.plan; return true; }
+    const Knobs knobs = Knobs::read();
+    const int cus = device_cu_count();
+    struct Key { int64_t N, D, V, B; int cus, fa, fb, fc, fs; Plan plan; bool valid; };
+    static thread_local Key cache = {0, 0, 0, 0, 0, 0, 0, 0, 0, {}, false};
+    if (cache.valid && cache.N == N && cache.D == D && cache.V == V && cache.B == budget_rows && cache.cus == cus &&
+        cache.fa == knobs.row_tiles && cache.fb == knobs.vocab_tiles && cache.fc == knobs.gemm_cols &&
+        cache.fs == knobs.split_acc) { *p = cache.plan; return true; }
     const bool compact = budget_rows != 0;
 
-    const int cus = device_cu_count();
     const int64_t Np = round_up(N, 256), Vp = round_up(V, 256);
     p->TT = (int)(Np / 256);
     p->VT = (int)(Vp / 256);
@@ -151,7 +170,8 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     size_t budget = (size_t)((double)(compact ? budget_rows : N) * (double)V * 4.0 * 0.01);
     if (budget < kBudgetFloor) budget = kBudgetFloor;
     const size_t scalar_bytes = compact ? (size_t)round_up(Np * 4, 256) : 0;      // one per-row int32 / fp32 array
-    const size_t fixed = 256 + partial_bytes + (compact ? 256 + 4 * scalar_bytes : 0);
+    const size_t zero_row_bytes = compact ? (size_t)round_up(D * 2, 256) : 0;
+    const size_t fixed = 256 + partial_bytes + (compact ? 256 + 4 * scalar_bytes + zero_row_bytes : 0);
 
     // Row block of a tiles, vocabulary chunk of b tiles.
     int acc_bytes = 4;          // per element of the dH running sum: 4 (fp32) or 2 (split planes)
@@ -161,10 +181,10 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     // Tiling for a given contraction tile: the (a, b) with the smallest modelled time.
     auto plan_for_kind = [&](int kind, int* a_out, int* b_out) -> double {
         BackwardModel model{cus, D, gemm_tile_of_kind(kind)};
-        if (g_force_row_tiles > 0 && g_force_vocab_tiles > 0) {
-            *a_out = g_force_row_tiles < p->TT ? g_force_row_tiles : p->TT;
+        if (knobs.row_tiles > 0 && knobs.vocab_tiles > 0) {
+            *a_out = knobs.row_tiles < p->TT ? knobs.row_tiles : p->TT;
             if (compact && *a_out > kCompactMaxRowTiles) *a_out = kCompactMaxRowTiles;
-            *b_out = g_force_vocab_tiles < p->VT ? g_force_vocab_tiles : p->VT;
+            *b_out = knobs.vocab_tiles < p->VT ? knobs.vocab_tiles : p->VT;
             return 0.0;
         }
         double best_cost = 1e300;
@@ -200,8 +220,8 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
         acc_bytes = bytes;
         double cost = 0.0;
         *kind_out = 1;
-        if (g_force_gemm_cols != 0) {
-            *kind_out = g_force_gemm_cols == 256 ? 0 : 1;
+        if (knobs.gemm_cols != 0) {
+            *kind_out = knobs.gemm_cols == 256 ? 0 : 1;
             if (*kind_out == 0) cost = plan_for_kind(0, a_out, b_out);
         } else if (D % 256 == 0) {
             cost = plan_for_kind(0, a_out, b_out);
@@ -218,7 +238,7 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     const double cost_f32 = plan_for_acc(4, &best_a, &best_b, &best_kind);
     const double cost_split = plan_for_acc(2, &sa, &sb, &skind);
     p->split_acc = 0;
-    if (g_force_split_acc == 2 || (g_force_split_acc == 0 && cost_split < 0.97 * cost_f32)) {
+    if (knobs.split_acc == 2 || (knobs.split_acc == 0 && cost_split < 0.97 * cost_f32)) {
         best_a = sa; best_b = sb; best_kind = skind; p->split_acc = 1;
     }
     acc_bytes = p->split_acc ? 2 : 4;
@@ -239,16 +259,17 @@ static bool make_plan(int64_t N, int64_t D, int64_t V, Plan* p, int64_t budget_r
     p->off_g = p->off_dhacc + (size_t)round_up(p->Nb * D * (p->split_acc ? 2 : 4), 256);
     p->total = p->off_g + (size_t)(p->Nb * p->Vc * 2);
     p->rows_pad = Np;
-    p->off_count = p->off_perm = p->off_labels_c = p->off_fa_c = p->off_fb_c = 0;
+    p->off_count = p->off_perm = p->off_labels_c = p->off_fa_c = p->off_fb_c = p->off_zero_row = 0;
     if (compact) {
         p->off_count = round_up((int64_t)p->total, 256);
         p->off_perm = p->off_count + 256;
         p->off_labels_c = p->off_perm + scalar_bytes;
         p->off_fa_c = p->off_labels_c + scalar_bytes;
         p->off_fb_c = p->off_fa_c + scalar_bytes;
-        p->total = p->off_fb_c + scalar_bytes;
+        p->off_zero_row = p->off_fb_c + scalar_bytes;
+        p->total = p->off_zero_row + zero_row_bytes;
     }
-    cache = {N, D, V, budget_rows, g_force_row_tiles, g_force_vocab_tiles, g_force_gemm_cols, g_force_split_acc, *p, true};
+    cache = {N, D, V, budget_rows, cus, knobs.row_tiles, knobs.vocab_tiles, knobs.gemm_cols, knobs.split_acc, *p, true};
     return true;
 }
 
