@@ -63,7 +63,8 @@ enum {
     CCE_OK = 0,
     CCE_ERR_INVALID = -1,      /* null pointer, N/D/V <= 0, misaligned pointer, workspace too small */
     CCE_ERR_UNSUPPORTED = -2,  /* D not a multiple of 64, or a size beyond 32-bit tile indexing */
-    CCE_ERR_HIP = -3           /* a HIP call or kernel launch failed (see cce_last_hip_error) */
+    CCE_ERR_HIP = -3,          /* a HIP call or kernel launch failed (see cce_last_hip_error) */
+    CCE_ERR_TOO_LARGE = -4     /* cce_forward_static: the shape needs more than CCE_STATIC_SCRATCH_BYTES */
 };
 
 enum {
@@ -104,6 +105,30 @@ int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
                 int64_t N, int64_t D, int64_t V, int32_t ignore_index,
                 float* loss, float* lse,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * cce_forward without a workspace argument and without any allocation -- for callers that cannot
+ * allocate device memory or size a workspace where they call it: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results (bit for bit)
+ * as cce_forward; the scratch the forward needs (status word and the per-vocabulary-split
+ * (max, sum-exp) pairs, 12 bytes x N x splits) lives in a static device array of
+ * CCE_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until
+ * the process ends.
+ *   hidden, weight, labels, N, D, V, ignore_index, loss, lse, stream   as in cce_forward
+ *   status   out int32 [1]  device, may be NULL: the call's status word (bit set of CCE_STATUS_*),
+ *            cleared and written by this call's kernels -- read it after the stream work is done
+ * Returns CCE_ERR_TOO_LARGE when N x splits does not fit the static array (N = 8192 .. 32768 of
+ * the benchmark shapes need 0.8 MB; the limit is reached near N x splits = 1.39 million), the
+ * other codes as cce_forward.  Calls no hipMalloc / hipFree or allocating routine; the first call
+ * on a device looks the array's address up (hipGetSymbolAddress) and raises the kernels' LDS
+ * limit, so make one call outside a graph capture first.  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (two streams, two threads) race on it and give
+ * undefined results -- serialise them.  Nothing in the array needs to survive between calls.
+ */
+#define CCE_STATIC_SCRATCH_BYTES (16u << 20)
+int cce_forward_static(const void* hidden, const void* weight, const int32_t* labels,
+                       int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                       float* loss, float* lse, int32_t* status, void* stream);
 
 /*
  * Backward (CCE backward theorem; chunk-level backward algorithm).

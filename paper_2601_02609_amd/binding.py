@@ -18,12 +18,14 @@ CCE_OK = 0
 CCE_ERR_INVALID = -1
 CCE_ERR_UNSUPPORTED = -2
 CCE_ERR_HIP = -3
+CCE_ERR_TOO_LARGE = -4
+STATIC_SCRATCH_BYTES = 16 << 20
 CCE_STATUS_BAD_LABEL = 1
 
 EXPORTED_SYMBOLS = [
     "cce_version", "cce_strerror", "cce_last_hip_error", "cce_workspace_bytes",
     "cce_materialised_logit_bytes", "cce_forward", "cce_backward", "cce_read_status",
-    "cce_forward_ex", "cce_backward_ex",
+    "cce_forward_ex", "cce_backward_ex", "cce_forward_static",
     "cce_profile_begin", "cce_profile_end", "cce_set_backward_tiling",
     "cce_get_backward_tiling", "cce_get_backward_gemm_tile", "cce_set_backward_gemm_tile",
     "cce_set_backward_accumulator", "cce_get_backward_accumulator",
@@ -84,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.cce_forward_ex.argtypes = [vp, vp, vp, i64, i64, i64, i32, f32, f32, vp, vp, vp, vp, sz, vp]
     L.cce_backward_ex.restype = ctypes.c_int
     L.cce_backward_ex.argtypes = [vp, vp, vp, vp, vp, f32, i64, i64, i64, i32, f32, f32, vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_forward_static.restype = ctypes.c_int
+    L.cce_forward_static.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, vp]
     L.cce_read_status.restype = ctypes.c_int
     L.cce_read_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     L.cce_profile_begin.restype = ctypes.c_int
@@ -211,6 +215,28 @@ def cce_forward(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor
     if rc != CCE_OK:
         raise CCEError(rc, "cce_forward")
     return loss, lse
+
+
+def cce_forward_static(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,
+                       ignore_index: int, loss: torch.Tensor, lse: torch.Tensor,
+                       status: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+    """cce_forward with the library's static scratch: no workspace, and nothing is allocated here
+    either -- every output is the caller's (loss, lse fp32 [N]; status int32 [1] or None)."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    if status is not None:
+        _check(status, torch.int32, (1,), "status")
+    rc = lib().cce_forward_static(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), N, D, V,
+                                  ignore_index, loss.data_ptr(), lse.data_ptr(),
+                                  status.data_ptr() if status is not None else None, _stream_ptr(stream))
+    if rc != CCE_OK:
+        raise CCEError(rc, "cce_forward_static")
 
 
 def cce_backward(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor,

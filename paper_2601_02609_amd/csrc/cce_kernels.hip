@@ -968,6 +968,7 @@ const char* cce_strerror(int code) {
         case CCE_ERR_INVALID: return "invalid argument (null or misaligned pointer, non-positive size, workspace too small)";
         case CCE_ERR_UNSUPPORTED: return "unsupported shape (D must be a multiple of 64; tensors must stay below 4 GiB of bf16)";
         case CCE_ERR_HIP: return "HIP runtime error (see cce_last_hip_error)";
+        case CCE_ERR_TOO_LARGE: return "problem needs more scratch than the static buffer of cce_forward_static holds (use cce_forward with a workspace)";
         default: return "unknown error code";
     }
 }
@@ -1005,7 +1006,8 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
                         float label_smoothing, float z_loss,
                         float* loss, float* lse, float* mean_loss,
                         int64_t v_off, float* stats, bool want_sumz, const Fp8Scales* fp8_in,
-                        void* workspace, size_t workspace_bytes, void* stream_, const CompactCtx* cc = nullptr) {
+                        void* workspace, size_t workspace_bytes, void* stream_, const CompactCtx* cc = nullptr,
+                        int32_t* status_word = nullptr) {
     Plan p;
     Fp8Scales fp8 = {nullptr, nullptr, 0, 0};
     if (fp8_in) {
@@ -1026,7 +1028,7 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
     }
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)workspace;
-    int32_t* status = (int32_t*)(ws + p.off_status);
+    int32_t* status = status_word ? status_word : (int32_t*)(ws + p.off_status);
     float2* partials = (float2*)(ws + p.off_partials);
     const bool smooth = stats ? want_sumz : label_smoothing != 0.f;
     float* sumz = smooth ? (float*)(ws + p.off_sumz) : (float*)nullptr;
@@ -1102,6 +1104,47 @@ int cce_forward(const void* hidden, const void* weight, const int32_t* labels,
                 float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
     return cce_forward_ex(hidden, weight, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
                           workspace, workspace_bytes, stream_);
+}
+
+// ------------------------------------------------------------------------------------------
+// cce_forward for callers that cannot allocate or bring a workspace: the forward's scratch (status
+// word, per-split (max, sum-exp) pairs) lives in a file-scope device array.  In host code the
+// array's name is only a handle: its device address is looked up once per device with
+// hipGetSymbolAddress and that address, never the name, is what kernels and plans are given.
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[CCE_STATIC_SCRATCH_BYTES];
+
+// Device address of this device's copy of `scratch` (each GPU holds its own), or nullptr.
+static void* static_scratch_address() {
+    static std::mutex mu;
+    static void* address[64] = {};
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev)) || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch))) || !ptr) return nullptr;
+        address[dev] = ptr;
+    }
+    return address[dev];
+}
+
+int cce_forward_static(const void* hidden, const void* weight, const int32_t* labels,
+                       int64_t N, int64_t D, int64_t V, int32_t ignore_index,
+                       float* loss, float* lse, int32_t* status, void* stream_) {
+    if (!hidden || !weight || !labels || !loss || !lse) return CCE_ERR_INVALID;
+    if (N <= 0 || D <= 0 || V <= 0 || ((uintptr_t)status & 3)) return CCE_ERR_INVALID;
+    if (D % 64 != 0) return CCE_ERR_UNSUPPORTED;
+    Plan p;
+    if (!make_plan(N, D, V, &p)) return CCE_ERR_INVALID;
+    // the forward touches the workspace up to the end of the partial results only
+    if (p.off_dhacc > (size_t)CCE_STATIC_SCRATCH_BYTES) return CCE_ERR_TOO_LARGE;
+    void* ws = static_scratch_address();
+    if (!ws) return CCE_ERR_HIP;
+    // forward_impl checks a workspace against the whole plan (forward + backward); only the part
+    // in front of off_dhacc exists here and only that part is addressed by the forward kernels
+    return forward_impl(hidden, weight, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+                        0, nullptr, false, nullptr, ws, p.total, stream_, nullptr, status);
 }
 
 // Backward over the V rows of `weight`, which are the rows [v_off, v_off + V) of a matrix of
