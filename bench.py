@@ -8,6 +8,11 @@ of the dominant kernel family measured with HIP events inside the timed steps, a
 fp64 CPU oracle timed on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen05b] [--no-cpu-baseline]
+                    [--no-other-configs] [--calibrate-matmul] [--calibrate-copy] [--all-rows]
+
+After the headline region the other full-size configurations (1b, 7b, smallv) are timed as well
+(3 steps each, inputs generated on the box from the seed) and reported under `other_configs`;
+`value` stays the headline workload.
 """
 from __future__ import annotations
 
@@ -50,6 +55,11 @@ def main() -> int:
                     help="time cce_forward + cce_backward (every row goes through the kernels) as the headline "
                          "instead of the row-skipping entry points")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the timing of the other full-size configurations (1b, 7b, smallv)")
+    ap.add_argument("--calibrate-matmul", action="store_true",
+                    help="also time the vendor GEMM (torch.matmul, bf16) at 8192^3 and at the forward's own shape, on "
+                         "random and on constant data: the calibration of what a plain GEMM sustains on this device")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
@@ -258,12 +268,97 @@ def main() -> int:
     # what the peak is divided by: the nominal figure, the one the device properties give
     # (compute units x 4096 flop/clock x clock), and a register-only MFMA loop on this device
     cus, khz = B.device_info()
+    # register-only loop on operands loaded once from memory: the same instruction stream on random
+    # normal values and on constants -- the difference is the device's response to operand activity
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    probe_rand = torch.randn(512 * 48, device=dev, generator=gen).bfloat16()
+    B.mfma_probe_data_tflops(probe_rand, iters=4000)          # clocks up
     peak_info = {
         "nominal_tflops": MFMA_BF16_PEAK_TFLOPS,
         "from_device_properties_tflops": round(cus * 4096 * khz * 1e3 / 1e12, 1),
         "compute_units": cus, "clock_mhz": khz // 1000,
-        "register_only_mfma_loop_tflops": round(B.mfma_probe_tflops(), 1),
+        "register_only_mfma_loop_tflops": round(B.mfma_probe_tflops(iters=20000), 1),
+        "register_only_random_operands_tflops": round(B.mfma_probe_data_tflops(probe_rand, iters=20000), 1),
+        "register_only_constant_operands_tflops": round(B.mfma_probe_data_tflops(torch.full_like(probe_rand, 0.5), iters=20000), 1),
+        "register_only_zero_operands_tflops": round(B.mfma_probe_data_tflops(torch.zeros_like(probe_rand), iters=20000), 1),
     }
+    roofline["practical_peak"] = {
+        "register_only_random_operands_tflops": peak_info["register_only_random_operands_tflops"],
+        "note": "rate of a register-only MFMA loop on random bf16 operands on this device (no LDS, no memory): what the "
+                "matrix cores sustain at the clock the device holds under operand activity; `frac` stays against the nominal peak"}
+
+    matmul_cal = None
+    if args.calibrate_matmul:
+        def mm_tflops(M, Nn, K, kind, reps=10):
+            if kind == "random":
+                a = torch.randn(M, K, device=dev).bfloat16()
+                b = torch.randn(Nn, K, device=dev).bfloat16()
+            else:
+                a = torch.full((M, K), 0.5, device=dev).bfloat16()
+                b = torch.full((Nn, K), 0.25, device=dev).bfloat16()
+            c = a @ b.T
+            torch.cuda.synchronize()
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record()
+            for _ in range(reps):
+                c = a @ b.T
+            t1.record()
+            torch.cuda.synchronize()
+            del a, b, c
+            return round(2.0 * M * Nn * K * reps / (t0.elapsed_time(t1) * 1e-3) / 1e12, 1)
+        matmul_cal = {f"{m}x{n}x{k}_{kind}": mm_tflops(m, n, k, kind)
+                      for (m, n, k) in ((8192, 8192, 8192), (8192, 151936, 896), (16384, 8192, 4096))
+                      for kind in ("random", "constant")}
+        matmul_cal["what"] = "torch.matmul (vendor GEMM) bf16 TFLOP/s, M x N x K, random normal vs constant operands"
+
+    # The other full-size configurations, through the entry points the library itself would pick
+    # (row skipping where its planner rates it faster, else all rows): 3 timed steps each after one
+    # warm-up step.  Inputs are generated here from the seed; the headline tensors are freed first.
+    other_configs = None
+    if not args.no_other_configs and args.workload == "qwen05b":
+        del H, W, y, dl, ws, wc, loss, lse, dH, dW, gam, yn, dxn, rstd, dgam, nws, sws, ssq
+        torch.cuda.empty_cache()
+        other_configs = {}
+        for name in ("1b", "7b", "smallv"):
+            wo = I.make_config(name)
+            No, Do, Vo = wo.spec.N, wo.spec.D, wo.spec.V
+            Ho = torch.from_numpy(wo.hidden.view(np.int16)).to(dev).view(torch.bfloat16)
+            Wo = torch.from_numpy(wo.weight.view(np.int16)).to(dev).view(torch.bfloat16)
+            yo = torch.from_numpy(wo.labels).to(dev)
+            dlo = torch.from_numpy(wo.dloss_mean).to(dev)
+            nv = int(((wo.labels != wo.spec.ignore_index) & (wo.labels >= 0) & (wo.labels < Vo)).sum())
+            skip_o = bool(B.get_row_skipping(No, Do, Vo, nv))
+            wso = B.alloc_compact_workspace(No, Do, Vo, nv) if skip_o else B.alloc_workspace(No, Do, Vo)
+            lo = torch.empty(No, dtype=torch.float32, device=dev)
+            so = torch.empty(No, dtype=torch.float32, device=dev)
+            dHo = torch.empty(No, Do, dtype=torch.bfloat16, device=dev)
+            dWo = torch.empty(Vo, Do, dtype=torch.float32, device=dev)
+
+            def step_o():
+                if skip_o:
+                    B.cce_forward_compact(Ho, Wo, yo, nv, wo.spec.ignore_index, workspace=wso, loss=lo, lse=so)
+                    B.cce_backward_compact(Ho, Wo, yo, so, dlo, nv, wo.spec.ignore_index, workspace=wso, d_hidden=dHo, d_weight=dWo)
+                else:
+                    B.cce_forward(Ho, Wo, yo, wo.spec.ignore_index, workspace=wso, loss=lo, lse=so)
+                    B.cce_backward(Ho, Wo, yo, so, dlo, wo.spec.ignore_index, workspace=wso, d_hidden=dHo, d_weight=dWo)
+            us = timed_us(step_o, reps=3)
+            assert B.read_status(wso) == 0 and bool(torch.isfinite(lo).all())
+            rows_o = nv if skip_o else No
+            tf = 8.0 * rows_o * Vo * Do / (us * 1e-6) / 1e12
+            other_configs[name] = {
+                "N": No, "D": Do, "V": Vo, "n_valid": nv, "ms_per_step": round(us * 1e-3, 3),
+                "tokens_per_s": round(No / (us * 1e-6), 1),
+                "rows_computed": int(rows_o), "tflops_executed": round(tf, 1),
+                "pct_bf16_mfma_peak": round(100 * tf / MFMA_BF16_PEAK_TFLOPS, 2),
+                "workspace_bytes": int(wso.numel()),
+                "workspace_pct_of_logits": round(100.0 * wso.numel() / B.materialised_logit_bytes(No, Vo), 3),
+                "entry_points": "cce_forward_compact + cce_backward_compact" if skip_o else "cce_forward + cce_backward",
+                "backward_tiling_256": list(B.get_compact_tiling(No, Do, Vo, nv) if skip_o else B.get_backward_tiling(No, Do, Vo)),
+                "backward_gemm_tile": list(B.get_backward_gemm_tile(nv if skip_o else No, Do, Vo)),
+                "steps": 3, "mean_loss": round(float(lo.sum().item()) / max(nv, 1), 5)}
+            del wo, Ho, Wo, yo, dlo, wso, lo, so, dHo, dWo
+            torch.cuda.empty_cache()
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -302,7 +397,8 @@ def main() -> int:
         "workspace_pct_of_logits": round(100.0 * ws_used.numel() / B.materialised_logit_bytes(N, V), 3),
         "backward_tiling_256": list(B.get_compact_tiling(N, D, V, n_valid) if skipping else B.get_backward_tiling(N, D, V)),
         "mean_loss": round(mean_loss, 5),
-        "roofline": roofline, "cpu_baseline": cpu, "around_the_path_hbm": aux, "fp8_variant": fp8, "other_path": other_path, "mfma_peak": peak_info,
+        "roofline": roofline, "cpu_baseline": cpu, "other_configs": other_configs, "around_the_path_hbm": aux,
+        "fp8_variant": fp8, "other_path": other_path, "mfma_peak": peak_info, "matmul_calibration": matmul_cal,
     }
     print(json.dumps(out))
     return 0
