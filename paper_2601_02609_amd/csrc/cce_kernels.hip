@@ -668,33 +668,40 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
     fetch_old(0);
 
     if (Cfg::KG == 2) {
-        // the two K groups hold partial sums of the same positions: group 1 parks its
-        // accumulators in the staging area, group 0 adds them to its own
-        if (wave_kg<Cfg>() == 1) {
+        // The two K groups hold partial sums of the same positions.  Each wavefront finalises half
+        // of its blocks (K group g the blocks bm with bm / (TM / 2) == g): it hands the other half
+        // to its partner through the staging area, at the positions the sums end up in, then adds
+        // what the partner left at its own positions and puts the sums there, in place (a lane
+        // reads and rewrites its own words only).  All eight wavefronts work in both steps; a + b
+        // is the same value whichever group adds.
+        static_assert(Cfg::KG == 1 || Cfg::TM % 2 == 0, "blocks split evenly between the K groups");
+        const int kg = wave_kg<Cfg>();
 #pragma unroll
-            for (int bm = 0; bm < Cfg::TM; ++bm)
+        for (int bm = 0; bm < Cfg::TM; ++bm) {
+            if (bm / (Cfg::TM / 2) == kg) continue;
 #pragma unroll
-                for (int bn = 0; bn < Cfg::TN; ++bn)
+            for (int bn = 0; bn < Cfg::TN; ++bn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        *(CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
+                for (int r = 0; r < 16; ++r)
+                    *(CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4) = acc[bm][bn][r];
         }
         barrier_lds_only();
-        if (wave_kg<Cfg>() == 0) {
 #pragma unroll
-            for (int bm = 0; bm < Cfg::TM; ++bm)
+        for (int bm = 0; bm < Cfg::TM; ++bm) {
+            if (bm / (Cfg::TM / 2) != kg) continue;
 #pragma unroll
-                for (int bn = 0; bn < Cfg::TN; ++bn)
+            for (int bn = 0; bn < Cfg::TN; ++bn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[bm][bn][r] += *(const CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4);
+                for (int r = 0; r < 16; ++r) {
+                    CCE_LDS float* pos = (CCE_LDS float*)(smem + acc_row<Cfg>(bm, r) * kRowBytes + acc_col<Cfg>(bn) * 4);
+                    *pos = acc[bm][bn][r] + *pos;
+                }
         }
-        // group 0 overwrites exactly the words it has just read, so no barrier is needed here
     }
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) {
         const int pr0 = pass * kRowsPerPass;
-        if (wave_kg<Cfg>() == 0) {
+        if (Cfg::KG == 1) {
 #pragma unroll
             for (int bm = 0; bm < Cfg::TM; ++bm) {
                 const int brow = wave_row0 + bm * 32;           // the 32-row block lies in one pass
