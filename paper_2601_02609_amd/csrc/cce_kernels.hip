@@ -516,7 +516,10 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
                 union { __bf16 h[4]; u32x2 u; } pk;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) pk.h[e] = (__bf16)g[e];
-                *(CCE_LDS u32x2*)(smem + col * kGRowBytes + vrow * 2) = pk.u;
+                // (token rows with bit 3 set keep the two 8-byte halves of every 16-byte chunk swapped:
+                // with a row pitch that is a multiple of 16 bytes, rows c and c + 8 of the 16 lanes
+                // an 8-byte write serves per cycle would otherwise hit the same LDS banks)
+                *(CCE_LDS u32x2*)(smem + col * kGRowBytes + ((vrow * 2) ^ (col & 8))) = pk.u;
             }
         }
         barrier_lds_only();
@@ -528,7 +531,10 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
             const int row = (idx >> 5) * (Cfg::TN * 32) + bn * 32 + (idx & 31);
             const bool live = live_flags[row] != 0;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (live) v = *(const CCE_LDS u32x4*)(smem + row * kGRowBytes + chunk * 16);
+            if (live) {
+                v = *(const CCE_LDS u32x4*)(smem + row * kGRowBytes + chunk * 16);
+                if (row & 8) v = u32x4{v.z, v.w, v.x, v.y};           // undo the half swap of the staging writes
+            }
             *(u32x4*)(G + (size_t)(ti * Cfg::BN + row) * ldg + (size_t)vi * Cfg::BM + chunk * 8) = v;
         }
     }
