@@ -140,3 +140,75 @@ def test_graph_capture_of_the_variants(B, which):
             assert torch.equal(ref[k], b[k]), (which, rep, k)
         assert float(junk) == float(junk)
     B.set_row_skipping(0)
+
+
+def test_two_host_threads_on_two_streams(B):
+    """The library is called from more than one thread: two threads, each with its own stream, shapes,
+    workspace and outputs, run forward + backward at the same time; every result equals what the same
+    thread's inputs give when run alone.  (Plans are cached per thread, kernel set-up and the process-wide
+    knobs are behind locks / atomics.)"""
+    import threading
+    specs = [I.custom_spec(700, 896, 3000, seed=45, ignore_frac=0.2), I.custom_spec(520, 256, 2100, seed=46, ignore_frac=0.1)]
+    loads = [I.make_workload(sp) for sp in specs]
+    refs = []
+    for w in loads:
+        r = _buffers(B, w)
+        _step(B, r)
+        refs.append(r)
+    torch.cuda.synchronize()
+    outs = [_buffers(B, w) for w in loads]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    errors = []
+
+    def worker(i):
+        try:
+            torch.cuda.set_device(0)
+            for _ in range(6):
+                for k in ("loss", "lse", "dH", "dW"):
+                    outs[i][k].zero_()              # on the default stream of this thread's context: ordered below
+                streams[i].wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(streams[i]):
+                    _step(B, outs[i], stream=streams[i])
+                streams[i].synchronize()
+                for k in ("loss", "lse", "dH", "dW"):
+                    if not torch.equal(refs[i][k], outs[i][k]):
+                        errors.append((i, k))
+        except Exception as exc:                    # surfaced in the main thread
+            errors.append((i, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads)
+    assert errors == []
+
+
+def test_static_forward_under_graph_capture(B):
+    """cce_forward_static is for callers that cannot allocate, code under graph capture among them:
+    captured (after one call outside a capture), replayed three times with eager work in between, every
+    replay equal to cce_forward."""
+    w = I.make_workload(I.custom_spec(520, 128, 2100, seed=47, ignore_frac=0.1))
+    H, W, y = dev_inputs(w)
+    ref_loss, ref_lse = B.cce_forward(H, W, y, IGN)
+    loss = torch.empty(520, device="cuda")
+    lse = torch.empty(520, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.cce_forward_static(H, W, y, IGN, loss, lse, status)          # first use outside a capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            B.cce_forward_static(H, W, y, IGN, loss, lse, status, stream=s)
+    for rep in range(3):
+        loss.zero_()
+        lse.zero_()
+        status.fill_(77)
+        junk = torch.randn(1 << 20, device="cuda").sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss, ref_loss) and torch.equal(lse, ref_lse) and int(status.item()) == 0, rep
+        assert float(junk) == float(junk)
