@@ -16,8 +16,11 @@
  *
  * Conventions are those of cce.h.  A row is valid when its label lies in [0, V) and is not
  * ignore_index.  If there are MORE valid rows than max_valid_rows the surplus rows (the last
- * ones) are dropped, CCE_STATUS_ROW_BOUND is set in the workspace status word and the results
- * are incomplete -- check cce_read_status where the bound is not certain.  (Where the calls
+ * ones) are dropped: they are treated like ignored rows (loss = lse = 0, a zero dHidden row, no
+ * contribution to dW), CCE_STATUS_ROW_BOUND is set in the workspace status word and the results
+ * are those of the kept rows only -- check cce_read_status where the bound is not certain.
+ * The hidden row of a row that is not valid is never loaded by these calls, so it may hold
+ * anything, NaN and Inf included (cce_forward / cce_backward ask for finite values there).  (Where the calls
  * decide not to skip rows, see cce_get_row_skipping, every row is processed and nothing is
  * dropped or flagged.)  max_valid_rows >= N
  * is allowed (nothing is skipped then).
