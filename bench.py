@@ -3,7 +3,7 @@
 
 A step is one cce_forward + cce_backward over one batch of the Qwen2.5-0.5B LM-head
 shape (N = 8192 tokens, D = 896, V = 151936; seeded synthetic inputs, already resident in
-HBM).  Prints ONE JSON line: tokens/s (the metric the benchmark spec names), the MFMA roofline
+HBM).  Prints ONE JSON line: tokens/s (the headline metric of this build), the MFMA roofline
 of the dominant kernel family measured with HIP events inside the timed steps, and the
 fp64 CPU oracle timed on a bounded sample of the same workload.
 
