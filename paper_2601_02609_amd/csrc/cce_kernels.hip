@@ -56,6 +56,31 @@ __device__ __forceinline__ int xcd_round_id(int bid, int nb, int round) {
     return base + xcd_linear_id(bid - base, n);
 }
 
+// Two jobs in one grid that is larger than the resident set: the first n1 work items are long (the
+// job with the longer reduction), the other n2 short.  Workgroup ids reach the XCDs round robin and
+// every XCD starts its own ids in order as its compute units become free, so what an XCD runs is
+// the QUEUE of ids congruent to it modulo 8.  Each queue gets an equal share of the long items,
+// first, then an equal share of the short ones -- consecutive items of a job stay on one XCD (they
+// share an operand band in its L2) -- so that every XCD has short items to back-fill with while its
+// long items run.  (Mapping rounds of 256 ids instead hands the first XCDs nothing but long items:
+// their queued short items then wait for a whole long reduction while the other XCDs idle --
+// measured at N = 16384, D = 2048: 314 us per launch instead of 235.)  Needs n1, n2 >= 8.
+__device__ __forceinline__ void xcd_two_job_map(int bid, int n1, int n2, bool& in_first, int& item) {
+    const int x = bid & 7, slot = bid >> 3;
+    const int q1 = n1 >> 3, r1 = n1 & 7;
+    const int c1 = q1 + (x < r1 ? 1 : 0);                 // long items of this XCD
+    if (slot < c1) {
+        in_first = true;
+        item = x * q1 + (x < r1 ? x : r1) + slot;
+        return;
+    }
+    const int n = n1 + n2, q = n >> 3, r = n & 7;
+    int before = 0;                                        // short items of the XCDs before this one
+    for (int xx = 0; xx < x; ++xx) before += (q + (xx < r ? 1 : 0)) - (q1 + (xx < r1 ? 1 : 0));
+    in_first = false;
+    item = before + (slot - c1);
+}
+
 // Linear index -> (i, j) over an n_i x n_j grid, walking i fastest inside groups of `group`
 // consecutive i, then j, then the next group (the last group may be narrower).
 __device__ __forceinline__ void group_map(int lin, int n_i, int n_j, int group, int& i, int& j) {
@@ -757,10 +782,16 @@ template <class Cfg, int MODE>
 __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first, const GemmJob second) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
-    const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
-    const bool in_first = lin < first.n_work;
+    bool in_first;
+    int item;
+    if ((int)gridDim.x > 256 && first.n_work >= 8 && second.n_work >= 8) {
+        xcd_two_job_map(blockIdx.x, first.n_work, second.n_work, in_first, item);
+    } else {
+        const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
+        in_first = lin < first.n_work;
+        item = in_first ? lin : lin - first.n_work;
+    }
     const GemmJob& j = in_first ? first : second;
-    const int item = in_first ? lin : lin - first.n_work;
     if (j.a_kmajor) run_gemm_job<Cfg, true, MODE>(j, item, smem);
     else run_gemm_job<Cfg, false, (MODE & 2)>(j, item, smem);
 }
