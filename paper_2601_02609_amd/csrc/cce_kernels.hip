@@ -56,15 +56,18 @@ __device__ __forceinline__ int xcd_round_id(int bid, int nb, int round) {
     return base + xcd_linear_id(bid - base, n);
 }
 
-// Two jobs in one grid that is larger than the resident set: the first n1 work items are long (the
-// job with the longer reduction), the other n2 short.  Workgroup ids reach the XCDs round robin and
+// Two jobs in one grid: the first n1 work items are long (the job with the longer reduction), the
+// other n2 short.  Workgroup ids reach the XCDs round robin and
 // every XCD starts its own ids in order as its compute units become free, so what an XCD runs is
 // the QUEUE of ids congruent to it modulo 8.  Each queue gets an equal share of the long items,
 // first, then an equal share of the short ones -- consecutive items of a job stay on one XCD (they
 // share an operand band in its L2) -- so that every XCD has short items to back-fill with while its
 // long items run.  (Mapping rounds of 256 ids instead hands the first XCDs nothing but long items:
 // their queued short items then wait for a whole long reduction while the other XCDs idle --
-// measured at N = 16384, D = 2048: 314 us per launch instead of 235.)  Needs n1, n2 >= 8.
+// measured at N = 16384, D = 2048: 314 us per launch instead of 235.  A grid that fits the machine
+// in one round gains too, less: when the short items end, every XCD keeps the same number of long
+// ones running instead of four XCDs going idle beside four full ones -- 2.7 % per launch at
+// N = 8192, D = 896.)  Needs n1, n2 >= 8.
 __device__ __forceinline__ void xcd_two_job_map(int bid, int n1, int n2, bool& in_first, int& item) {
     const int x = bid & 7, slot = bid >> 3;
     const int q1 = n1 >> 3, r1 = n1 & 7;
@@ -573,8 +576,8 @@ __global__ __launch_bounds__(kThreads) void grad_tile_kernel(
 // A is the scratch chunk G (zero padded to tile multiples in both directions), B is a slice
 // of an input tensor in K-slow layout.  The result is added to / stored in the job's output
 // (see GemmJob for its two forms).  Rows >= m_valid and columns >= n_valid are
-// dropped.  Workgroups [0, first.n_work) serve the first job, the rest the second; the host
-// puts the job with the longer reduction first so that its tiles are dispatched first.
+// dropped.  The host puts the job with the longer reduction first; xcd_two_job_map deals the items
+// of both jobs to the workgroup ids so that every XCD starts with its share of the long ones.
 // ------------------------------------------------------------------------------------------
 // LDS of grad_gemm_kernel: the main loop's stages or the epilogue staging, whichever is larger.
 constexpr int gemm_lds_bytes(int main_loop, int bm, int bn) {
@@ -784,7 +787,7 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
     CCE_LDS char* smem = (CCE_LDS char*)smem_generic;
     bool in_first;
     int item;
-    if ((int)gridDim.x > 256 && first.n_work >= 8 && second.n_work >= 8) {
+    if (first.n_work >= 8 && second.n_work >= 8) {
         xcd_two_job_map(blockIdx.x, first.n_work, second.n_work, in_first, item);
     } else {
         const int lin = xcd_round_id(blockIdx.x, gridDim.x, 256);
