@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcce.so")
 SOURCES = [os.path.join(CSRC, "cce_kernels.hip"), os.path.join(CSRC, "aux_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "gemm_core.h"), os.path.join(CSRC, "host_util.h"), os.path.join(CSRC, "plan.h"),
+HEADERS = [os.path.join(CSRC, "gemm_core.h"), os.path.join(CSRC, "host_util.h"), os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "wg_map.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce_aux.h"),
            os.path.join(os.path.dirname(PKG_DIR), "include", "cce_shard.h"),

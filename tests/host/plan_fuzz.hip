@@ -3,6 +3,8 @@
 // UndefinedBehaviorSanitizer on the HOST side only (tests/test_plan_host.py compiles and runs it; no
 // GPU is needed: without a device the planner assumes 256 compute units).  Every plan must lay the
 // workspace out without overlap, inside its budget, with aligned offsets and tile-multiple blocks.
+// The workgroup-id -> work-item mappings of the kernels (csrc/wg_map.h) are walked here as well: for
+// every grid size a launch can have, each mapping must hit every item exactly once.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -10,6 +12,8 @@
 
 namespace cce { thread_local int g_last_hip_error = 0; }
 #include "../../paper_2601_02609_amd/csrc/plan.h"
+#include "../../paper_2601_02609_amd/csrc/wg_map.h"
+#include <vector>
 
 using namespace cce;
 
@@ -69,8 +73,65 @@ static void check_plan(int64_t N, int64_t D, int64_t V, int64_t budget_rows, boo
     CHECK(p.model_us >= 0.0, "model");
 }
 
+// Every workgroup id of a grid maps to a distinct item inside the grid (a repeated or out-of-range item
+// would be a tile computed twice, one never computed, or a store outside the output).
+static void check_maps() {
+    std::vector<int> seen;
+    for (int nb = 1; nb <= 2600; ++nb) {
+        seen.assign(nb, 0);
+        for (int b = 0; b < nb; ++b) {
+            const int l = xcd_round_id(b, nb, 256);
+            CHECK(l >= 0 && l < nb, "xcd_round_id nb=%d b=%d -> %d", nb, b, l);
+            if (l >= 0 && l < nb) ++seen[l];
+        }
+        for (int l = 0; l < nb; ++l) CHECK(seen[l] == 1, "xcd_round_id nb=%d item %d hit %d times", nb, l, seen[l]);
+        if (nb <= 256) {
+            // one round: the ids of one XCD (equal modulo 8) take consecutive items
+            for (int b = 8; b < nb; ++b) CHECK(xcd_linear_id(b, nb) == xcd_linear_id(b - 8, nb) + 1, "xcd_linear_id nb=%d b=%d", nb, b);
+        }
+    }
+    // two jobs in one grid: n1 long items, then n2 short ones, both >= 8
+    for (int n1 = 8; n1 <= 420; n1 += (n1 < 80 ? 1 : 7)) {
+        for (int n2 = 8; n2 <= 1400; n2 += (n2 < 80 ? 1 : 11)) {
+            std::vector<int> s1(n1, 0), s2(n2, 0);
+            int long_per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int b = 0; b < n1 + n2; ++b) {
+                bool in_first = false; int item = -1;
+                xcd_two_job_map(b, n1, n2, in_first, item);
+                const int n = in_first ? n1 : n2;
+                CHECK(item >= 0 && item < n, "two_job n1=%d n2=%d b=%d -> %d/%d", n1, n2, b, (int)in_first, item);
+                if (item < 0 || item >= n) continue;
+                ++(in_first ? s1 : s2)[item];
+                if (in_first) {
+                    ++long_per_xcd[b & 7];
+                    // an XCD starts its ids in order: its long items come before its short ones
+                    CHECK((b >> 3) < (n1 + 7) / 8, "long item late in the queue n1=%d n2=%d b=%d", n1, n2, b);
+                }
+            }
+            for (int i = 0; i < n1; ++i) CHECK(s1[i] == 1, "two_job n1=%d n2=%d long item %d hit %d times", n1, n2, i, s1[i]);
+            for (int i = 0; i < n2; ++i) CHECK(s2[i] == 1, "two_job n1=%d n2=%d short item %d hit %d times", n1, n2, i, s2[i]);
+            for (int x = 0; x < 8; ++x)
+                CHECK(long_per_xcd[x] == n1 / 8 || long_per_xcd[x] == n1 / 8 + 1, "uneven deal n1=%d n2=%d xcd %d: %d", n1, n2, x, long_per_xcd[x]);
+        }
+    }
+    // (i fastest inside groups of `group`) x j: every cell of the n_i x n_j grid exactly once
+    for (int n_i = 1; n_i <= 70; ++n_i)
+        for (int n_j = 1; n_j <= 40; n_j += (n_j < 12 ? 1 : 9))
+            for (int group = 1; group <= 9; group += 3) {
+                seen.assign(n_i * n_j, 0);
+                for (int lin = 0; lin < n_i * n_j; ++lin) {
+                    int i = -1, j = -1;
+                    group_map(lin, n_i, n_j, group, i, j);
+                    CHECK(i >= 0 && i < n_i && j >= 0 && j < n_j, "group_map %d x %d group %d lin %d -> (%d, %d)", n_i, n_j, group, lin, i, j);
+                    if (i >= 0 && i < n_i && j >= 0 && j < n_j) ++seen[i * n_j + j];
+                }
+                for (int c = 0; c < n_i * n_j; ++c) CHECK(seen[c] == 1, "group_map %d x %d group %d cell %d hit %d times", n_i, n_j, group, c, seen[c]);
+            }
+}
+
 int main(int argc, char** argv) {
     const int iters = argc > 1 ? atoi(argv[1]) : 3000;
+    check_maps();
     // the five benchmark shapes first
     const int64_t shapes[5][3] = {{256, 64, 1000}, {8192, 896, 151936}, {16384, 2048, 151936}, {32768, 3584, 151936}, {16384, 4096, 32000}};
     for (auto& s : shapes) {

@@ -1,7 +1,9 @@
 """Host logic of the library under sanitizers: the planner (csrc/plan.h) is compiled into a small
 harness (tests/host/plan_fuzz.hip) with AddressSanitizer and UndefinedBehaviorSanitizer on the host
 side only, and swept over seeded shapes, forced tilings, contraction tiles, accumulator forms and
-row-skipping budgets.  No GPU: without a device the planner assumes 256 compute units."""
+row-skipping budgets; the same harness walks the workgroup-id -> work-item mappings of the kernels
+(csrc/wg_map.h) over every grid size and checks that each is one-to-one.  No GPU: without a device the
+planner assumes 256 compute units."""
 import os
 import shutil
 import subprocess
