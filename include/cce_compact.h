@@ -67,6 +67,28 @@ int cce_backward_compact(const void* hidden, const void* weight, const int32_t* 
                          void* dHidden, float* dW, int accumulate_dW,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* The loss variants of cce_forward_ex / cce_backward_ex (label smoothing, z-loss, mean reduction:
+ * smoothed cross-entropy definition, z-loss definition and gradient proposition, the division by the
+ * number of non-ignored rows in the paper's cross-entropy kernel) over the valid rows only -- the
+ * paper's kernel has both in one: it returns early for an ignored row and applies the variants to
+ * the others.  Arguments as in cce_forward_ex / cce_backward_ex plus max_valid_rows; results are
+ * theirs up to fp32 summation order.  The mean (mean_loss; dloss == NULL in the backward) is taken
+ * over the rows that took part: the valid rows, or the kept ones where the bound dropped some
+ * (CCE_STATUS_ROW_BOUND).  cce_forward_compact / cce_backward_compact are these calls with
+ * label_smoothing = z_loss = 0, no mean_loss, grad_scale = 1. */
+int cce_forward_compact_ex(const void* hidden, const void* weight, const int32_t* labels,
+                           int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                           float label_smoothing, float z_loss,
+                           float* loss, float* lse, float* mean_loss,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+int cce_backward_compact_ex(const void* hidden, const void* weight, const int32_t* labels,
+                            const float* lse, const float* dloss, float grad_scale,
+                            int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                            float label_smoothing, float z_loss,
+                            void* dHidden, float* dW, int accumulate_dW,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,6 +38,7 @@ EXPORTED_SYMBOLS = [
     "cce_shard_forward", "cce_shard_merge", "cce_shard_backward",
     # include/cce_compact.h
     "cce_compact_workspace_bytes", "cce_forward_compact", "cce_backward_compact",
+    "cce_forward_compact_ex", "cce_backward_compact_ex",
     "cce_get_row_skipping", "cce_set_row_skipping", "cce_get_compact_tiling",
     # include/cce_fp8.h
     "cce_fp8_scale_bytes", "cce_quantize_e4m3", "cce_fp8_forward", "cce_fp8_backward",
@@ -149,6 +150,12 @@ def lib() -> ctypes.CDLL:
     L.cce_forward_compact.argtypes = [vp, vp, vp, i64, i64, i64, i32, i64, vp, vp, vp, sz, vp]
     L.cce_backward_compact.restype = ctypes.c_int
     L.cce_backward_compact.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i64, vp, vp, ctypes.c_int, vp, sz, vp]
+    L.cce_forward_compact_ex.restype = ctypes.c_int
+    L.cce_forward_compact_ex.argtypes = [vp, vp, vp, i64, i64, i64, i32, i64, ctypes.c_float, ctypes.c_float,
+                                         vp, vp, vp, vp, sz, vp]
+    L.cce_backward_compact_ex.restype = ctypes.c_int
+    L.cce_backward_compact_ex.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i64, i64, i32, i64,
+                                          ctypes.c_float, ctypes.c_float, vp, vp, ctypes.c_int, vp, sz, vp]
     L.cce_fp8_scale_bytes.restype = sz
     L.cce_fp8_scale_bytes.argtypes = [i64, i64]
     L.cce_quantize_e4m3.restype = ctypes.c_int
@@ -853,4 +860,65 @@ def cce_backward_compact(hidden: torch.Tensor, weight: torch.Tensor, labels: tor
                                    dloss.data_ptr(), N, D, V, ignore_index, max_valid_rows,
                                    d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
                                    workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_backward_compact")
+    return d_hidden, d_weight
+
+
+def cce_forward_compact_ex(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor, max_valid_rows: int,
+                           ignore_index: int = -100, *, label_smoothing: float = 0.0, z_loss: float = 0.0,
+                           want_mean: bool = False, workspace: Optional[torch.Tensor] = None,
+                           loss: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                           stream: Optional[torch.cuda.Stream] = None):
+    """Loss variants of the forward over the valid rows only: (loss [N], lse [N], mean_loss [1] or None)."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    if workspace is None:
+        workspace = alloc_compact_workspace(N, D, V, max_valid_rows, hidden.device)
+    if loss is None:
+        loss = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    _check(loss, torch.float32, (N,), "loss")
+    _check(lse, torch.float32, (N,), "lse")
+    mean = torch.empty(1, dtype=torch.float32, device=hidden.device) if want_mean else None
+    _rc(lib().cce_forward_compact_ex(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), N, D, V, ignore_index,
+                                     max_valid_rows, label_smoothing, z_loss, loss.data_ptr(), lse.data_ptr(),
+                                     mean.data_ptr() if mean is not None else None,
+                                     workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_forward_compact_ex")
+    return loss, lse, mean
+
+
+def cce_backward_compact_ex(hidden: torch.Tensor, weight: torch.Tensor, labels: torch.Tensor, lse: torch.Tensor,
+                            dloss: Optional[torch.Tensor], max_valid_rows: int, ignore_index: int = -100, *,
+                            grad_scale: float = 1.0, label_smoothing: float = 0.0, z_loss: float = 0.0,
+                            workspace: Optional[torch.Tensor] = None,
+                            d_hidden: Optional[torch.Tensor] = None, d_weight: Optional[torch.Tensor] = None,
+                            accumulate_dw: bool = False,
+                            stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Loss variants of the backward over the valid rows only; dloss=None selects mean reduction."""
+    N, D = hidden.shape
+    V = weight.shape[0]
+    _check(hidden, torch.bfloat16, (N, D), "hidden")
+    _check(weight, torch.bfloat16, (V, D), "weight")
+    _check(labels, torch.int32, (N,), "labels")
+    _check(lse, torch.float32, (N,), "lse")
+    if dloss is not None:
+        _check(dloss, torch.float32, (N,), "dloss")
+    if workspace is None:
+        workspace = alloc_compact_workspace(N, D, V, max_valid_rows, hidden.device)
+    if d_hidden is None:
+        d_hidden = torch.empty(N, D, dtype=torch.bfloat16, device=hidden.device)
+    if d_weight is None:
+        if accumulate_dw:
+            raise ValueError("accumulate_dw needs an existing d_weight")
+        d_weight = torch.empty(V, D, dtype=torch.float32, device=hidden.device)
+    _check(d_hidden, torch.bfloat16, (N, D), "d_hidden")
+    _check(d_weight, torch.float32, (V, D), "d_weight")
+    _rc(lib().cce_backward_compact_ex(hidden.data_ptr(), weight.data_ptr(), labels.data_ptr(), lse.data_ptr(),
+                                      dloss.data_ptr() if dloss is not None else None, grad_scale,
+                                      N, D, V, ignore_index, max_valid_rows, label_smoothing, z_loss,
+                                      d_hidden.data_ptr(), d_weight.data_ptr(), 1 if accumulate_dw else 0,
+                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "cce_backward_compact_ex")
     return d_hidden, d_weight

@@ -334,12 +334,14 @@ __global__ __launch_bounds__(1024) void mean_scale_kernel(const int32_t* __restr
 
 // Mean of the per-token losses over the non-ignored rows (0 when there are none).  One
 // workgroup; each thread sums a strided subset in fp32, then a fixed tree: the result is
-// reproducible run to run.
+// reproducible run to run.  `kept` (optional, device): the number of rows that took part, where
+// that is not the number of valid labels (row skipping with a bound that dropped rows).
 __global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict__ loss, const int32_t* __restrict__ labels,
-                                                         int N, int V, int32_t ignore_index, float* __restrict__ out) {
+                                                         int N, int V, int32_t ignore_index, float* __restrict__ out,
+                                                         const int32_t* __restrict__ kept) {
     __shared__ int scratch[16];
     __shared__ float fsum[16];
-    const int n = count_valid_rows(labels, N, V, ignore_index, scratch);
+    const int n = kept ? kept[0] : count_valid_rows(labels, N, V, ignore_index, scratch);
     float a = 0.f;
     for (int i = threadIdx.x; i < N; i += blockDim.x) a += loss[i];     // ignored rows hold 0
 #pragma unroll
@@ -1046,7 +1048,7 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
                        (int)v_off, (float4*)stats, fp8, fwd_perm);
     if (mean_loss && !stats)
         hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
-                           (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss);
+                           (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss, (const int32_t*)nullptr);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
@@ -1083,7 +1085,7 @@ int cce_shard_merge(const float* stats, int P, const int32_t* labels, int64_t N,
                        loss, lse, status);
     if (mean_loss)
         hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
-                           (const float*)loss, labels, (int)N, (int)V_total, ignore_index, mean_loss);
+                           (const float*)loss, labels, (int)N, (int)V_total, ignore_index, mean_loss, (const int32_t*)nullptr);
     if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
     return CCE_OK;
 }
@@ -1350,16 +1352,19 @@ size_t cce_compact_workspace_bytes(int64_t N, int64_t D, int64_t V, int64_t max_
     return p.total;
 }
 
-int cce_forward_compact(const void* hidden, const void* weight, const int32_t* labels,
-                        int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
-                        float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+int cce_forward_compact_ex(const void* hidden, const void* weight, const int32_t* labels,
+                           int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                           float label_smoothing, float z_loss,
+                           float* loss, float* lse, float* mean_loss,
+                           void* workspace, size_t workspace_bytes, void* stream_) {
     CompactCtx cc;
-    if (!loss || !lse || (((uintptr_t)loss | (uintptr_t)lse) & 3)) return CCE_ERR_INVALID;
+    if (!loss || !lse || (((uintptr_t)loss | (uintptr_t)lse | (uintptr_t)mean_loss) & 3)) return CCE_ERR_INVALID;
+    if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     bool use_compact = false;
     int rc = compact_plan(hidden, weight, labels, N, D, V, max_valid_rows, workspace, workspace_bytes, &cc.plan, &use_compact);
     if (rc != CCE_OK) return rc;
     if (!use_compact)
-        return forward_impl(hidden, weight, labels, N, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
+        return forward_impl(hidden, weight, labels, N, D, V, ignore_index, label_smoothing, z_loss, loss, lse, mean_loss,
                             0, nullptr, false, nullptr, workspace, workspace_bytes, stream_);
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     const Plan& p = cc.plan;
@@ -1376,23 +1381,38 @@ int cce_forward_compact(const void* hidden, const void* weight, const int32_t* l
                        (uint16_t*)nullptr, 0);
     // the kernels fetch hidden rows through perm and write loss / lse to the original rows
     cc.perm = perm;
-    return forward_impl(hidden, weight, labels, M, D, V, ignore_index, 0.f, 0.f, loss, lse, nullptr,
-                        0, nullptr, false, nullptr, workspace, workspace_bytes, stream_, &cc);
+    rc = forward_impl(hidden, weight, labels, M, D, V, ignore_index, label_smoothing, z_loss, loss, lse, nullptr,
+                      0, nullptr, false, nullptr, workspace, workspace_bytes, stream_, &cc);
+    if (rc != CCE_OK || !mean_loss) return rc;
+    // mean over the rows that took part: the rows left out hold loss 0
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, stream,
+                       (const float*)loss, labels, (int)N, (int)V, ignore_index, mean_loss, (const int32_t*)(ws + p.off_count));
+    if (!hip_ok(hipGetLastError())) return CCE_ERR_HIP;
+    return CCE_OK;
 }
 
-int cce_backward_compact(const void* hidden, const void* weight, const int32_t* labels,
-                         const float* lse, const float* dloss,
-                         int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
-                         void* dHidden, float* dW, int accumulate_dW,
-                         void* workspace, size_t workspace_bytes, void* stream_) {
+int cce_forward_compact(const void* hidden, const void* weight, const int32_t* labels,
+                        int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                        float* loss, float* lse, void* workspace, size_t workspace_bytes, void* stream_) {
+    return cce_forward_compact_ex(hidden, weight, labels, N, D, V, ignore_index, max_valid_rows, 0.f, 0.f,
+                                  loss, lse, nullptr, workspace, workspace_bytes, stream_);
+}
+
+int cce_backward_compact_ex(const void* hidden, const void* weight, const int32_t* labels,
+                            const float* lse, const float* dloss, float grad_scale,
+                            int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                            float label_smoothing, float z_loss,
+                            void* dHidden, float* dW, int accumulate_dW,
+                            void* workspace, size_t workspace_bytes, void* stream_) {
     CompactCtx cc;
-    if (!lse || !dloss || !dHidden || !dW) return CCE_ERR_INVALID;
+    if (!lse || !dHidden || !dW) return CCE_ERR_INVALID;
     if (((uintptr_t)dHidden | (uintptr_t)dW) & 15) return CCE_ERR_INVALID;
+    if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     bool use_compact = false;
     int rc = compact_plan(hidden, weight, labels, N, D, V, max_valid_rows, workspace, workspace_bytes, &cc.plan, &use_compact);
     if (rc != CCE_OK) return rc;
     if (!use_compact)
-        return backward_impl(hidden, weight, labels, lse, dloss, 1.f, N, D, V, 0, V, ignore_index, 0.f, 0.f,
+        return backward_impl(hidden, weight, labels, lse, dloss, grad_scale, N, D, V, 0, V, ignore_index, label_smoothing, z_loss,
                              dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_);
     if (!ensure_kernel_attributes()) return CCE_ERR_HIP;
     const Plan& p = cc.plan;
@@ -1417,8 +1437,20 @@ int cce_backward_compact(const void* hidden, const void* weight, const int32_t* 
                        (const int32_t*)perm, (const int32_t*)(ws + p.off_count));
     cc.perm = perm;
     cc.zero_row = ws + p.off_zero_row;
-    return backward_impl(hidden, weight, labels_c, lse_c, dloss_c, 1.f, M, D, V, 0, V, ignore_index, 0.f, 0.f,
+    // mean reduction (dloss == NULL) counts the compact labels: the rows that take part
+    return backward_impl(hidden, weight, labels_c, lse_c, dloss ? dloss_c : (const float*)nullptr, grad_scale, M, D, V, 0, V,
+                         ignore_index, label_smoothing, z_loss,
                          dHidden, dW, accumulate_dW, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream_, &cc);
+}
+
+int cce_backward_compact(const void* hidden, const void* weight, const int32_t* labels,
+                         const float* lse, const float* dloss,
+                         int64_t N, int64_t D, int64_t V, int32_t ignore_index, int64_t max_valid_rows,
+                         void* dHidden, float* dW, int accumulate_dW,
+                         void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!dloss) return CCE_ERR_INVALID;
+    return cce_backward_compact_ex(hidden, weight, labels, lse, dloss, 1.f, N, D, V, ignore_index, max_valid_rows, 0.f, 0.f,
+                                   dHidden, dW, accumulate_dW, workspace, workspace_bytes, stream_);
 }
 
 int cce_fp8_forward(const void* hidden_q, const void* hidden_scales, const void* weight_q, const void* weight_scales,
