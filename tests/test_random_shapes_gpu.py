@@ -1,6 +1,8 @@
 """Seeded sweep over random shapes, ignore fractions, forced tilings, contraction tiles,
 accumulator forms and both entry-point families (all rows / row skipping) against the oracle:
-the fixed shapes of the other parity tests were chosen by hand, these were not."""
+the fixed shapes of the other parity tests were chosen by hand, these were not.  A second block
+draws larger shapes (contraction launches of more than one round of workgroups) and adds the loss
+variants and mean reduction through the _ex entry points of both families."""
 import numpy as np
 import pytest
 import torch
@@ -70,6 +72,74 @@ def test_random_case(B, case):
             g_loss, g_lse, g_dH = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), bf16_host(dH)
             assert np.max(np.abs(g_loss - o_loss)) <= LOSS_ATOL, family
             assert np.max(np.abs(g_lse[~ign] - o_lse[~ign])) <= LOSS_ATOL, family
+            assert np.all(g_loss[ign] == 0.0) and np.all(g_dH[ign] == 0.0), family
+            assert rel_fro(g_dH, o_dH) <= GRAD_RTOL, family
+            assert rel_fro(dW.cpu().numpy().astype(np.float64), o_dW) <= GRAD_RTOL, family
+    finally:
+        B.set_backward_tiling(0, 0)
+        B.set_backward_gemm_tile(0)
+        B.set_backward_accumulator(0)
+        B.set_row_skipping(0)
+
+
+def draw_wide_case(case):
+    """Larger draws (launches of more than one round of workgroups, hidden sizes up to 2048) with the
+    loss variants and mean reduction in the mix."""
+    rng = np.random.default_rng(5000 + case)
+    N = int(rng.integers(1, 6000))
+    D = 64 * int(rng.integers(1, 33))
+    V = int(rng.integers(2, 6000))
+    frac = float(rng.choice([0.0, 0.05, 0.3, 0.7, 0.95]))
+    rt = int(rng.integers(0, 9))
+    vt = int(rng.integers(1, 12)) if rt else 0
+    cols = int(rng.choice([0, 128, 256]))
+    acc = int(rng.choice([0, 1, 2]))
+    skip = int(rng.choice([0, 2]))
+    slack = int(rng.integers(0, 3))
+    eps = float(rng.choice([0.0, 0.0, 0.1]))
+    lam = float(rng.choice([0.0, 0.0, 1e-3]))
+    mean = bool(rng.integers(0, 2))
+    return N, D, V, frac, rt, vt, cols, acc, skip, slack, eps, lam, mean
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_wide_case(B, case):
+    N, D, V, frac, rt, vt, cols, acc, skip, slack, eps, lam, mean = draw_wide_case(case)
+    print(f"[random wide] case {case}: N={N} D={D} V={V} ignore={frac} tiling=({rt},{vt}) tile cols={cols} "
+          f"accumulator={acc} row skipping={skip} eps={eps} lambda={lam} mean={mean}", flush=True)
+    w = I.make_workload(I.custom_spec(N, D, V, seed=7000 + case, ignore_frac=frac))
+    H, W, y = dev_inputs(w)
+    o_loss, o_lse = O.forward(w.hidden, w.weight, w.labels, IGN, label_smoothing=eps, z_loss=lam)
+    dl_np = w.dloss_var if not mean else np.full(N, 1.0 / max(w.n_valid, 1), dtype=np.float32)
+    o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, dl_np, IGN, label_smoothing=eps, z_loss=lam)
+    ign = w.labels == IGN
+    dl = None if mean else torch.from_numpy(w.dloss_var).cuda()
+    try:
+        B.set_backward_tiling(rt, vt)
+        B.set_backward_gemm_tile(cols)
+        B.set_backward_accumulator(acc)
+        B.set_row_skipping(skip)
+        for family in ("all rows", "row skipping"):
+            loss = torch.full((N,), 7.0, device="cuda")
+            lse = torch.full((N,), 7.0, device="cuda")
+            dH = torch.full((N, D), 3.0, dtype=torch.bfloat16, device="cuda")
+            dW = torch.full((V, D), 3.0, dtype=torch.float32, device="cuda")
+            if family == "all rows":
+                ws = B.alloc_workspace(N, D, V)
+                B.cce_forward_ex(H, W, y, IGN, label_smoothing=eps, z_loss=lam, workspace=ws, loss=loss, lse=lse)
+                B.cce_backward_ex(H, W, y, lse, dl, IGN, label_smoothing=eps, z_loss=lam, workspace=ws, d_hidden=dH, d_weight=dW)
+            else:
+                bound = int(w.n_valid) + slack
+                ws = B.alloc_compact_workspace(N, D, V, bound)
+                B.cce_forward_compact_ex(H, W, y, bound, IGN, label_smoothing=eps, z_loss=lam, workspace=ws, loss=loss, lse=lse)
+                B.cce_backward_compact_ex(H, W, y, lse, dl, bound, IGN, label_smoothing=eps, z_loss=lam, workspace=ws,
+                                          d_hidden=dH, d_weight=dW)
+            torch.cuda.synchronize()
+            assert B.read_status(ws) == 0, family
+            g_loss, g_lse, g_dH = loss.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), bf16_host(dH)
+            assert np.max(np.abs(g_loss - o_loss)) <= LOSS_ATOL, family
+            if (~ign).any():
+                assert np.max(np.abs(g_lse[~ign] - o_lse[~ign])) <= LOSS_ATOL, family
             assert np.all(g_loss[ign] == 0.0) and np.all(g_dH[ign] == 0.0), family
             assert rel_fro(g_dH, o_dH) <= GRAD_RTOL, family
             assert rel_fro(dW.cpu().numpy().astype(np.float64), o_dW) <= GRAD_RTOL, family
