@@ -754,13 +754,17 @@ __global__ __launch_bounds__(kThreads) void grad_gemm_kernel(const GemmJob first
 // loss / lse of the rows that are not valid, and of valid rows that were dropped, are set to zero
 // when the pointers are given (a caller that does not poll the status word then sees a zero
 // contribution from a dropped row, not stale memory).  zero_row (optional): zero_row_len bf16 zeros
-// are written there.
+// are written there.  The status word is WRITTEN here (bad label / bound bits or 0): the scan is the
+// first launch of a row-skipping call and needs no clearing launch in front of it.
+// Each thread owns a contiguous run of rows; counts are scanned inside a wavefront with shuffles,
+// the sixteen wavefront totals through LDS: one barrier.
 __global__ __launch_bounds__(1024) void row_scan_kernel(
         const int32_t* __restrict__ labels, int N, int V, int32_t ignore_index, int max_rows, int rows_pad,
         int32_t* __restrict__ perm, int32_t* __restrict__ count_out, int32_t* __restrict__ status,
         float* __restrict__ loss, float* __restrict__ lse, uint16_t* __restrict__ zero_row, int zero_row_len) {
-    __shared__ int part[1024];
-    const int tid = threadIdx.x;
+    __shared__ int wave_total[16];
+    __shared__ int wave_bad[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per = (N + 1023) / 1024;
     const int i0 = tid * per < N ? tid * per : N, i1 = i0 + per < N ? i0 + per : N;
     int c = 0, bad = 0;
@@ -770,16 +774,25 @@ __global__ __launch_bounds__(1024) void row_scan_kernel(
         c += (y != ignore_index && in_range) ? 1 : 0;
         bad |= (y != ignore_index && !in_range) ? 1 : 0;
     }
-    part[tid] = c;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {            // inclusive scan
-        const int v = tid >= o ? part[tid - o] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
+    int incl = c;                                     // inclusive scan over the lanes of the wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
     }
-    int pos = part[tid] - c;                          // exclusive prefix
-    const int total = part[1023];
+    const bool wave_has_bad = __ballot(bad != 0) != 0;
+    if (lane == 63) wave_total[wave] = incl;
+    if (lane == 0) wave_bad[wave] = wave_has_bad ? 1 : 0;
+    __syncthreads();
+    int before = 0, total = 0, any_bad = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int t = wave_total[w];
+        before += w < wave ? t : 0;
+        total += t;
+        any_bad |= wave_bad[w];
+    }
+    int pos = before + incl - c;                      // valid rows in front of this thread's run
     for (int i = i0; i < i1; ++i) {
         const int32_t y = labels[i];
         bool zero = true;
@@ -796,51 +809,39 @@ __global__ __launch_bounds__(1024) void row_scan_kernel(
         for (int c = tid; c < zero_row_len; c += 1024) zero_row[c] = 0;
     const int kept = total < max_rows ? total : max_rows;
     for (int r = kept + tid; r < rows_pad; r += 1024) perm[r] = -1;
-    if (bad) atomicOr(status, CCE_STATUS_BAD_LABEL);
     if (tid == 0) {
         count_out[0] = kept;
-        if (total > max_rows) atomicOr(status, CCE_STATUS_ROW_BOUND);
+        status[0] = (any_bad ? CCE_STATUS_BAD_LABEL : 0) | (total > max_rows ? CCE_STATUS_ROW_BOUND : 0);
     }
 }
 
-// Per-row scalars into the compact row space: labels (ignore_index for padding), and up to two
-// fp32 vectors (0 for padding).
-__global__ __launch_bounds__(256) void gather_scalars_kernel(const int32_t* __restrict__ perm, int rows_pad,
-        const int32_t* __restrict__ labels, int32_t ignore_index, int32_t* __restrict__ labels_c,
-        const float* __restrict__ a, float* __restrict__ a_c, const float* __restrict__ b, float* __restrict__ b_c) {
+// Backward of the row-skipping calls, after the scan, in one launch:
+// (a) per-row scalars into the compact row space: labels (ignore_index for padding) and up to two
+//     fp32 vectors (0 for padding) -- thread r of the grid handles compact row r;
+// (b) zero rows of dHidden for every row that takes no part: label not valid, or a valid row that
+//     the compaction dropped because the caller's bound was too small (the compaction is stable, so
+//     those are the valid rows behind the last kept one) -- one wavefront per original row.
+// Grid: enough workgroups of 256 for both, i.e. max(ceil(rows_pad / 256), ceil(N / 4)).
+__global__ __launch_bounds__(256) void compact_prepare_backward_kernel(
+        const int32_t* __restrict__ perm, const int32_t* __restrict__ count, int rows_pad,
+        const int32_t* __restrict__ labels, int N, int V, int32_t ignore_index, int32_t* __restrict__ labels_c,
+        const float* __restrict__ a, float* __restrict__ a_c, const float* __restrict__ b, float* __restrict__ b_c,
+        int D, uint16_t* __restrict__ dhidden) {
     const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r >= rows_pad) return;
-    const int from = perm[r];
-    labels_c[r] = from >= 0 ? labels[from] : ignore_index;
-    if (a) a_c[r] = from >= 0 ? a[from] : 0.f;
-    if (b) b_c[r] = from >= 0 ? b[from] : 0.f;
-}
-
-// loss / lse of the compact rows back to their original rows.
-__global__ __launch_bounds__(256) void scatter_scalars_kernel(const int32_t* __restrict__ perm, int rows_pad,
-        const float* __restrict__ a_c, float* __restrict__ a, const float* __restrict__ b_c, float* __restrict__ b) {
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r >= rows_pad) return;
-    const int to = perm[r];
-    if (to < 0) return;
-    a[to] = a_c[r];
-    b[to] = b_c[r];
-}
-
-// Zero rows of dHidden for every row that takes no part: label not valid, or a valid row that the
-// compaction dropped because the caller's bound was too small (the compaction is stable, so those
-// are the valid rows behind the last kept one).  One wavefront per row.
-__global__ __launch_bounds__(256) void zero_invalid_rows_kernel(const int32_t* __restrict__ labels, int N, int V,
-                                                                int32_t ignore_index, int D, uint16_t* __restrict__ out,
-                                                                const int32_t* __restrict__ perm, const int32_t* __restrict__ count) {
+    if (r < rows_pad) {
+        const int from = perm[r];
+        labels_c[r] = from >= 0 ? labels[from] : ignore_index;
+        if (a) a_c[r] = from >= 0 ? a[from] : 0.f;
+        if (b) b_c[r] = from >= 0 ? b[from] : 0.f;
+    }
     const int l = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= N) return;
-    const int32_t y = labels[r];
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const int32_t y = labels[row];
     const int kept = count[0];
     const int last_kept = kept > 0 ? perm[kept - 1] : -1;
-    if (y != ignore_index && y >= 0 && y < V && r <= last_kept) return;
-    u32x4* dr = (u32x4*)(out + (size_t)r * D);
+    if (y != ignore_index && y >= 0 && y < V && row <= last_kept) return;
+    u32x4* dr = (u32x4*)(dhidden + (size_t)row * D);
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (int c = l; c < (D >> 3); c += 64) dr[c] = z;
 }
@@ -1012,7 +1013,7 @@ static int forward_impl(const void* hidden, const void* weight, const int32_t* l
     if (!variant_ok(label_smoothing, z_loss)) return CCE_ERR_INVALID;
     if (v_off < 0 || v_off > (1 << 30)) return CCE_ERR_INVALID;
     if (cc) {
-        p = cc->plan;           // arguments were checked, the status word cleared, by the caller
+        p = cc->plan;           // arguments were checked, the status word written (by the label scan), by the caller
     } else {
         int rc = check_common(hidden, weight, labels, N, D, V, workspace, workspace_bytes, &p);
         if (rc != CCE_OK) return rc;
@@ -1375,7 +1376,7 @@ int cce_forward_compact_ex(const void* hidden, const void* weight, const int32_t
     int32_t* perm = (int32_t*)(ws + p.off_perm);
     const int rows_pad = (int)p.rows_pad;
     drop_stale_hip_error();
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
+    // (the scan writes the status word: no clearing launch)
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
                        (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status, loss, lse,
                        (uint16_t*)nullptr, 0);
@@ -1426,15 +1427,16 @@ int cce_backward_compact_ex(const void* hidden, const void* weight, const int32_
     float* dloss_c = (float*)(ws + p.off_fb_c);
     const int rows_pad = (int)p.rows_pad;
     drop_stale_hip_error();
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, stream, status);
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, labels, (int)N, (int)V, ignore_index,
                        (int)(max_valid_rows < N ? max_valid_rows : N), rows_pad, perm, (int32_t*)(ws + p.off_count), status,
                        (float*)nullptr, (float*)nullptr, (uint16_t*)(ws + p.off_zero_row), (int)D);
-    hipLaunchKernelGGL(gather_scalars_kernel, dim3((unsigned)((rows_pad + 255) / 256)), dim3(256), 0, stream,
-                       (const int32_t*)perm, rows_pad, labels, ignore_index, labels_c, lse, lse_c, dloss, dloss_c);
-    hipLaunchKernelGGL(zero_invalid_rows_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream,
-                       labels, (int)N, (int)V, ignore_index, (int)D, (uint16_t*)dHidden,
-                       (const int32_t*)perm, (const int32_t*)(ws + p.off_count));
+    {
+        const unsigned g_gather = (unsigned)((rows_pad + 255) / 256), g_zero = (unsigned)((N + 3) / 4);
+        hipLaunchKernelGGL(compact_prepare_backward_kernel, dim3(g_gather > g_zero ? g_gather : g_zero), dim3(256), 0, stream,
+                           (const int32_t*)perm, (const int32_t*)(ws + p.off_count), rows_pad,
+                           labels, (int)N, (int)V, ignore_index, labels_c, lse, lse_c, dloss, dloss_c,
+                           (int)D, (uint16_t*)dHidden);
+    }
     cc.perm = perm;
     cc.zero_row = ws + p.off_zero_row;
     // mean reduction (dloss == NULL) counts the compact labels: the rows that take part
