@@ -240,7 +240,8 @@ int cce_profile_begin(void);
 int cce_profile_end(double* ms_out, int64_t* launches_out);
 
 /* Copies the workspace status word (bit set of CCE_STATUS_*) to *status_out (host).
- * Synchronises `stream`.  The word is cleared at the start of every cce_forward. */
+ * Synchronises `stream`.  The word is cleared at the start of every cce_forward; the row-skipping
+ * calls (cce_compact.h), forward and backward, set it anew from their label scan. */
 int cce_read_status(const void* workspace, void* stream, int32_t* status_out);
 
 #ifdef __cplusplus
