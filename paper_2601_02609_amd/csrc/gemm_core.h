@@ -90,6 +90,16 @@ __device__ __forceinline__ void load16_to_lds(const char* g, CCE_LDS char* lds_w
                  :: "v"(g), "s"(m0) : "memory", "m0");
 }
 
+// The same load with the address split as the instruction takes it: a wave-uniform 64-bit base in
+// scalar registers plus a 32-bit per-lane byte offset; m0_value is the wave-uniform LDS destination.
+// With the base advanced per K slice on the scalar unit and the per-lane offsets constant, a load
+// costs no vector-ALU instruction at all (the full-address form above needs an offset add, a
+// 64-bit add and, for the LDS destination, an add and a readfirstlane per load).
+__device__ __forceinline__ void load16_to_lds_sbase(const char* uniform_base, uint32_t lane_offset, uint32_t m0_value) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_offset), "s"(uniform_base), "s"(m0_value) : "memory", "m0");
+}
+
 // One operand (R = 128 or 256 free indices) of one workgroup tile: global -> LDS.
 template <bool KMAJOR, int R>
 struct OperandTile {
@@ -98,6 +108,7 @@ struct OperandTile {
     uint32_t ld_bytes;      // leading dimension in bytes
     uint32_t off[NL];       // K-major: clamped row offset + swizzled chunk; K-slow: clamped column offset
     int krow[NL];           // K-slow: k-row inside a slice handled by load i
+    uint32_t slow_off[NL];  // K-slow: krow[i] * row pitch + off[i] (full slices are loaded from a uniform base)
     int k_last;             // K-slow: last valid k (rows beyond are clamped to it)
     const CCE_LDS int32_t* kmap;   // K-slow, optional: k-row k is matrix row kmap[k]; where it holds -1 the
     const char* kzero;             // row is read from kzero instead: a row of zeros as long as a matrix row
@@ -127,6 +138,7 @@ struct OperandTile {
                 }
                 off[i] = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
                 krow[i] = 0;
+                slow_off[i] = 0;
             }
         } else {
             constexpr int CR = R / 8;            // 16-byte chunks per k-row
@@ -140,13 +152,30 @@ struct OperandTile {
             for (int i = 0; i < NL; ++i) {
                 off[i] = (uint32_t)col * 2u;
                 krow[i] = (wave + 8 * i) * RPL + sub;
+                slow_off[i] = (uint32_t)krow[i] * ld_bytes + off[i];
             }
         }
     }
 
     // Issue this thread's loads of the K slice starting at k0 into `stage` (LDS).
     __device__ __forceinline__ void issue(CCE_LDS char* stage, int k0) const {
-        const int wave = threadIdx.x >> 6;
+        const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const uint32_t lds0 = (uint32_t)(uintptr_t)stage + (uint32_t)wave * 1024u;     // wave-uniform
+        if (KMAJOR) {
+            // uniform base = matrix base + this slice's K offset; lane offsets are those of init()
+            const char* sb = base + (size_t)((uint32_t)k0 * 2u);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) load16_to_lds_sbase(sb, off[i], lds0 + (uint32_t)i * 8192u);
+            return;
+        }
+        if (!kmap && k0 + 63 <= k_last) {
+            // a full slice of a K-slow operand: uniform base = row k0, lane offset = its k-row inside
+            // the slice times the row pitch plus its column offset
+            const char* sb = base + (size_t)k0 * ld_bytes;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) load16_to_lds_sbase(sb, slow_off[i], lds0 + (uint32_t)i * 8192u);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const char* g;
