@@ -176,6 +176,27 @@ struct OperandTile {
             for (int i = 0; i < NL; ++i) load16_to_lds_sbase(sb, slow_off[i], lds0 + (uint32_t)i * 8192u);
             return;
         }
+        if (kmap) {
+            // mapped k-rows: lane offset = mapped row times the row pitch plus the
+            // column offset, from the matrix base -- unless some lane of the wavefront has a k-row that
+            // maps to no row (only behind the last valid row of the whole problem), which takes the
+            // per-lane form below
+            int m[NL];
+            int any = 0;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                int k = k0 + krow[i];
+                k = k < k_last ? k : k_last;
+                m[i] = kmap[k];
+                any |= m[i];
+            }
+            if (__builtin_amdgcn_ballot_w64(any < 0) == 0) {
+#pragma unroll
+                for (int i = 0; i < NL; ++i)
+                    load16_to_lds_sbase(base, (uint32_t)m[i] * ld_bytes + off[i], lds0 + (uint32_t)i * 8192u);
+                return;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const char* g;
