@@ -587,7 +587,7 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
             Bop.kzero = j.zero_row;
         }
     }
-    gemm_mainloop<Cfg, A_KMAJOR, false>(acc, Aop, Bop, j.k_total, smem);
+    gemm_mainloop<Cfg, A_KMAJOR, false, true>(acc, Aop, Bop, j.k_total, smem);
 
     // Epilogue through LDS so that global memory sees 16-byte accesses along full rows:
     // the fp32 tile is staged [rows][BN + 8 floats] (the padding keeps the two 128-byte
