@@ -570,22 +570,21 @@ __device__ __forceinline__ void run_gemm_job(const GemmJob& j, int item, CCE_LDS
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bm][bn][r] = 0.f;
 
+    constexpr bool kMappedB = (MODE & 2) != 0 && !A_KMAJOR;        // row skipping, dW job
     OperandTile<A_KMAJOR, Cfg::BM> Aop;
-    OperandTile<false, Cfg::BN> Bop;
+    OperandTile<false, Cfg::BN, kMappedB> Bop;
     Aop.init(j.A, j.lda, mi * Cfg::BM, j.a_free_n, j.a_k_n);
     Bop.init(j.B, j.ldb, ni * Cfg::BN, j.n_valid, j.b_k_n);
     if constexpr ((MODE & 2) != 0 && !A_KMAJOR) {
         // row skipping, dW job: the reduction runs over the compact rows of the block, whose hidden
         // rows are scattered over the original tensor.  The block's row map is copied into LDS
         // (behind everything the kernel otherwise uses) and the operand loader looks each of its
-        // k-rows up there.
-        if (j.row_map) {
-            CCE_LDS int32_t* tab = (CCE_LDS int32_t*)(smem + gemm_lds_bytes(Cfg::kLdsBytes, Cfg::BM, Cfg::BN));
-            for (int i = threadIdx.x; i < j.b_k_n; i += kThreads) tab[i] = j.row_map[i];
-            __syncthreads();
-            Bop.kmap = tab;
-            Bop.kzero = j.zero_row;
-        }
+        // k-rows up there.  (The host gives every row-skipping launch its row map.)
+        CCE_LDS int32_t* tab = (CCE_LDS int32_t*)(smem + gemm_lds_bytes(Cfg::kLdsBytes, Cfg::BM, Cfg::BN));
+        for (int i = threadIdx.x; i < j.b_k_n; i += kThreads) tab[i] = j.row_map[i];
+        __syncthreads();
+        Bop.kmap = tab;
+        Bop.kzero = j.zero_row;
     }
     gemm_mainloop<Cfg, A_KMAJOR, false, true>(acc, Aop, Bop, j.k_total, smem);
 

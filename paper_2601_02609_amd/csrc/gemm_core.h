@@ -102,8 +102,10 @@ __device__ __forceinline__ void load16_to_lds_sbase(const char* uniform_base, ui
 }
 
 // One operand (R = 128 or 256 free indices) of one workgroup tile: global -> LDS.
-template <bool KMAJOR, int R>
+// MAPPED (K-slow only): the k-rows are reached through a row map (kmap, kzero).
+template <bool KMAJOR, int R, bool MAPPED = false>
 struct OperandTile {
+    static_assert(!(KMAJOR && MAPPED), "only a K-slow operand carries a k-row map");
     static constexpr int NL = R / 64;   // 16-byte loads per thread and K slice
     const char* base;       // matrix base address
     uint32_t ld_bytes;      // leading dimension in bytes
@@ -158,7 +160,13 @@ struct OperandTile {
         }
     }
 
-    // Issue this thread's loads of the K slice starting at k0 into `stage` (LDS).
+    // K slices [0, full_slices()) lie entirely inside the operand's valid K extent (every slice of a
+    // K-major operand does: its extent is padded to the slice).
+    __device__ __forceinline__ int full_slices() const { return KMAJOR ? 0x7fffffff : (k_last + 1) / kBK; }
+
+    // Issue this thread's loads of the K slice starting at k0 into `stage` (LDS).  FULL (compile time):
+    // the caller knows that the slice is one of full_slices().
+    template <bool FULL = false>
     __device__ __forceinline__ void issue(CCE_LDS char* stage, int k0) const {
         const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
         const uint32_t lds0 = (uint32_t)(uintptr_t)stage + (uint32_t)wave * 1024u;     // wave-uniform
@@ -169,7 +177,7 @@ struct OperandTile {
             for (int i = 0; i < NL; ++i) load16_to_lds_sbase(sb, off[i], lds0 + (uint32_t)i * 8192u);
             return;
         }
-        if (!kmap && k0 + 63 <= k_last) {
+        if (!MAPPED && (FULL || k0 + 63 <= k_last)) {
             // a full slice of a K-slow operand: uniform base = row k0, lane offset = its k-row inside
             // the slice times the row pitch plus its column offset
             const char* sb = base + (size_t)k0 * ld_bytes;
@@ -177,7 +185,7 @@ struct OperandTile {
             for (int i = 0; i < NL; ++i) load16_to_lds_sbase(sb, slow_off[i], lds0 + (uint32_t)i * 8192u);
             return;
         }
-        if (kmap) {
+        if constexpr (MAPPED) {
             // mapped k-rows: lane offset = mapped row times the row pitch plus the
             // column offset, from the matrix base -- unless some lane of the wavefront has a k-row that
             // maps to no row (only behind the last valid row of the whole problem), which takes the
@@ -207,7 +215,7 @@ struct OperandTile {
                 int k = k0 + krow[i];
                 k = k < k_last ? k : k_last;
                 g = base + (size_t)((uint32_t)k * ld_bytes + off[i]);
-                if (kmap) {
+                if constexpr (MAPPED) {
                     // a k-row that stands for no matrix row must not fetch one: whatever that row
                     // holds (NaN included) would meet the other operand's zero in the MFMA
                     const int mapped = kmap[k];
@@ -308,10 +316,8 @@ __device__ __forceinline__ void barrier_lds_only() {
 // visible to all and its first fragments can be read under those last MFMAs, and (b)
 // the current stage may be overwritten by the loads issued at the top of the next
 // iteration.
-template <class Cfg, bool A_KMAJOR, bool B_KMAJOR, bool PEEL = false>
-__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
-                                               const OperandTile<A_KMAJOR, Cfg::BM>& A,
-                                               const OperandTile<B_KMAJOR, Cfg::BN>& B,
+template <class Cfg, bool A_KMAJOR, bool B_KMAJOR, bool PEEL = false, class OpA, class OpB>
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN], const OpA& A, const OpB& B,
                                                int k_total, CCE_LDS char* smem) {
     constexpr int S = Cfg::STAGES;
     constexpr int kAhead = (S - 2) * Cfg::kLoadsPerSlice;    // loads that may stay in flight
@@ -341,15 +347,16 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     int cur_s = 0;                       // stage holding slice kt
     // One K slice.  more: slice kt + S - 1 exists and is requested during this one (a bool, or a
     // std::true_type / std::false_type where the caller knows it at compile time).
-    auto slice = [&](int kt, auto more_tag) {
+    auto slice = [&](int kt, auto more_tag, auto full_tag) {
         const bool MORE = more_tag;
+        constexpr bool FULL = decltype(full_tag)::value;      // the requested slice is a full one of both operands
         CCE_LDS char* cur = smem + cur_s * Cfg::kStage;
         const int nxt_s = (cur_s + 1 == S) ? 0 : cur_s + 1;
         CCE_LDS char* nxt = smem + nxt_s * Cfg::kStage;
         const int ld_s = (cur_s == 0) ? S - 1 : cur_s - 1;       // stage of slice kt - 1, free again
         if (MORE) {
-            A.issue(smem + ld_s * Cfg::kStage, (kt + S - 1) * kBK);
-            B.issue(smem + ld_s * Cfg::kStage + Cfg::kAStage, (kt + S - 1) * kBK);
+            A.template issue<FULL>(smem + ld_s * Cfg::kStage, (kt + S - 1) * kBK);
+            B.template issue<FULL>(smem + ld_s * Cfg::kStage + Cfg::kAStage, (kt + S - 1) * kBK);
         }
 #pragma unroll
         for (int kk = 0; kk < SPS; ++kk) {
@@ -386,11 +393,17 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[Cfg::TM][Cfg::TN],
         // The last S - 1 slices request nothing: peeled off, so that neither loop body branches on it.
         // Pays in the contraction kernels (2.0 - 2.6 % per launch); the forward and the gradient-tile
         // kernel were 0.5 - 1 % faster with the one loop below.
+        // Likewise the slices whose request is a full slice of both operands (all but a ragged last one)
+        // run a body whose loads need no clamping of k-rows, hence no branch.
         const int n_more = KT - (S - 1) > 0 ? KT - (S - 1) : 0;
-        for (int kt = 0; kt < n_more; ++kt) slice(kt, std::true_type{});
-        for (int kt = n_more; kt < KT; ++kt) slice(kt, std::false_type{});
+        const int fa_n = A.full_slices(), fb_n = B.full_slices();
+        int n_full = (fa_n < fb_n ? fa_n : fb_n) - (S - 1);          // request kt + S - 1 < full slices
+        n_full = n_full < 0 ? 0 : (n_full < n_more ? n_full : n_more);
+        for (int kt = 0; kt < n_full; ++kt) slice(kt, std::true_type{}, std::true_type{});
+        for (int kt = n_full; kt < n_more; ++kt) slice(kt, std::true_type{}, std::false_type{});
+        for (int kt = n_more; kt < KT; ++kt) slice(kt, std::false_type{}, std::false_type{});
     } else {
-        for (int kt = 0; kt < KT; ++kt) slice(kt, kt + S - 1 < KT);
+        for (int kt = 0; kt < KT; ++kt) slice(kt, kt + S - 1 < KT, std::false_type{});
     }
     barrier_pending_loads<0>();
 }
