@@ -163,3 +163,44 @@ def test_large_configs_sampled(B, name):
               f"max|colsum dW|={colsum:.2e}", flush=True)
         assert e_loss <= LOSS_ATOL and e_lse <= LOSS_ATOL and e_dH <= GRAD_RTOL
         assert e_dW <= GRAD_RTOL and e_dWq <= GRAD_RTOL
+
+
+def test_weight_matrix_beyond_2_gib(B):
+    """Maximum sizes: a weight matrix of 2.49 GB (V = 151936, D = 8192), whose byte offsets pass 2^31 -- the
+    kernels address a tensor with a 64-bit base and 32-bit unsigned offsets, which must hold up to the
+    4 GiB limit the library states -- with labels in the top rows of W.  Few token rows, so that the full
+    oracle is cheap; both entry-point families, element by element."""
+    N, D, V = 300, 8192, 151936
+    w = I.make_workload(I.custom_spec(N, D, V, seed=77, ignore_frac=0.2))
+    w.labels[:8] = [V - 1, V - 2, V - 300, V - 11000, V - 17000, 0, 1, 131073]
+    dloss = w.dloss_var.copy()
+    dloss[:8] = 1.0 / N                         # (rows that the draw had ignored carry NaN there)
+    assert w.weight.nbytes > (1 << 31)
+    H, W, y = dev_inputs(w)
+    dl = torch.from_numpy(dloss).cuda()
+    n_valid = int((w.labels != IGN).sum())
+    print(f"[full] big W: oracle on all {N} rows", flush=True)
+    o_loss, o_lse = O.forward(w.hidden, w.weight, w.labels, IGN)
+    o_dH, o_dW = O.backward(w.hidden, w.weight, w.labels, dloss, IGN)
+    try:
+        for family in ("all rows", "row skipping"):
+            B.set_row_skipping(1 if family == "all rows" else 2)
+            if family == "all rows":
+                ws = B.alloc_workspace(N, D, V)
+                loss, lse = B.cce_forward(H, W, y, IGN, workspace=ws)
+                dH, dW = B.cce_backward(H, W, y, lse, dl, IGN, workspace=ws)
+            else:
+                ws = B.alloc_compact_workspace(N, D, V, n_valid)
+                loss, lse = B.cce_forward_compact(H, W, y, n_valid, IGN, workspace=ws)
+                dH, dW = B.cce_backward_compact(H, W, y, lse, dl, n_valid, IGN, workspace=ws)
+            torch.cuda.synchronize()
+            assert B.read_status(ws) == 0
+            g_dW = dW.cpu().numpy().astype(np.float64)
+            e = (np.abs(loss.cpu().numpy() - o_loss).max(), np.abs(lse.cpu().numpy() - o_lse).max(),
+                 rel_fro(bf16_host(dH), o_dH), rel_fro(g_dW, o_dW), rel_fro(g_dW[V - 20000:], o_dW[V - 20000:]))
+            print(f"[full] big W {family}: max|dloss|={e[0]:.2e} max|dlse|={e[1]:.2e} relF(dH)={e[2]:.2e} "
+                  f"relF(dW)={e[3]:.2e} relF(dW, rows beyond 2 GiB)={e[4]:.2e}", flush=True)
+            assert e[0] <= LOSS_ATOL and e[1] <= LOSS_ATOL and e[2] <= GRAD_RTOL and e[3] <= GRAD_RTOL and e[4] <= GRAD_RTOL
+            del dW, g_dW, ws
+    finally:
+        B.set_row_skipping(0)
